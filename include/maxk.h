@@ -1,0 +1,143 @@
+/*
+ * libmaxk -- MaxK-GNN aggregation hot path for AMD MI355X (gfx950), C ABI.
+ *
+ *   H --maxk_topk_cbsr--> CBSR (sp_data, sp_index) --maxk_spgemm_fwd--> Y
+ *   dY + sp_index --maxk_sspmm_bwd--> dXs            (plus a dense SpMM baseline)
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; the library
+ *     borrows them for the call and never frees or retains them, except that a
+ *     maxk_graph keeps (aliases) the three CSR arrays it was created from: they
+ *     must stay alive and unchanged until maxk_graph_destroy.
+ *   - Dense matrices are row-major fp32 with leading dimension = dim.
+ *     sp_data / sp_index / dXs are row-major with leading dimension = k.
+ *   - sp_index element width is index_bytes in {1,2,4} (uint8 / uint16 / int32),
+ *     and dim must fit: dim <= 256, <= 65536, or any.  The paper uses uint8 when
+ *     the hidden width is small and 4-byte integers otherwise (Sec. 4.3).
+ *   - Outputs are OVERWRITTEN; the caller need not clear them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return; they do not synchronise the device.
+ *     The compute calls allocate nothing (per-graph workspaces are made by
+ *     maxk_graph_create / maxk_graph_reserve), with one exception stated at
+ *     maxk_graph_reserve.
+ *   - Return value: MAXK_OK (0) or a negative maxk_status.  Nothing throws,
+ *     aborts or prints.  N == 0 is a valid no-op.  Array CONTENTS are not
+ *     validated by the compute calls (NaN in H, column ids outside [0,N) and
+ *     sp_index outside [0,dim) are contract violations).
+ *   - Calls on one maxk_graph must not overlap in time (they share its workspace).
+ */
+#ifndef MAXK_H
+#define MAXK_H
+
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define MAXK_API __attribute__((visibility("default")))
+#else
+#define MAXK_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t maxk_status;
+enum {
+    MAXK_OK = 0,
+    MAXK_INVALID_ARGUMENT = -1, /* null pointer, negative size, k outside [1,dim], bad index_bytes, misaligned pointer */
+    MAXK_UNSUPPORTED = -2,      /* dim above MAXK_MAX_DIM */
+    MAXK_HIP_ERROR = -3,        /* a HIP call failed; see maxk_last_hip_error() */
+    MAXK_OUT_OF_MEMORY = -4
+};
+
+/* Largest hidden width the kernels are compiled for. */
+#define MAXK_MAX_DIM 1024
+
+/* Which kernel maxk_sspmm_bwd runs (see maxk_graph_set_bwd_mode). */
+enum {
+    MAXK_BWD_AUTO = 0,    /* library's choice (the faster one on MI355X) */
+    MAXK_BWD_PULL_CSC = 1,/* owner-computes over A^T stored as CSC: deterministic, no atomics */
+    MAXK_BWD_PUSH_CSR = 2 /* Alg. 2's dataflow: stage dY[i,:] on chip, push along row i of A with fp32 atomics */
+};
+
+typedef struct maxk_graph maxk_graph;
+
+/*
+ * Load-time preprocessing of the adjacency (the paper's O(n) partition of rows
+ * into edge groups, Sec. 4.1 "Warp Level Partition", done "during graph loading",
+ * Sec. 4.2).  Takes A in CSR on the device: d_rowptr int32[N+1], d_colidx
+ * int32[nnz], d_val fp32[nnz]; rows may be empty, columns need not be sorted,
+ * duplicates add.  Builds and owns: the degree-ordered work-item lists with hub
+ * rows split into bounded chunks, and A^T as CSC (value-carrying) for the
+ * backward pull kernel.  Synchronises `stream` (it copies rowptr to the host).
+ * Not part of the timed path.
+ */
+MAXK_API maxk_status maxk_graph_create(maxk_graph** out, int64_t N, int64_t nnz, const int32_t* d_rowptr,
+                              const int32_t* d_colidx, const float* d_val, void* stream);
+
+/* Frees everything the handle owns (not the caller's CSR).  NULL is a no-op. */
+MAXK_API maxk_status maxk_graph_destroy(maxk_graph* g);
+
+/*
+ * Pre-allocates the handle's partial-sum workspace for hidden width `dim` and
+ * MaxK `k`, so that later compute calls with dim' <= dim, k' <= k allocate
+ * nothing.  Without it, the first compute call needing a larger workspace grows
+ * it (one synchronous allocation), later ones reuse it.
+ */
+MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k);
+
+/* Selects the backward kernel (MAXK_BWD_*). */
+MAXK_API maxk_status maxk_graph_set_bwd_mode(maxk_graph* g, int32_t mode);
+
+/* Reads back sizes: any out pointer may be NULL. */
+MAXK_API maxk_status maxk_graph_info(const maxk_graph* g, int64_t* N, int64_t* nnz, int64_t* n_fwd_items,
+                            int64_t* n_split_rows, int64_t* max_degree, int64_t* workspace_bytes);
+
+/*
+ * MaxK nonlinearity + CBSR packing (Sec. 3.1 definition, Eq. 1; CBSR: Sec. 3.2
+ * "Forward Computation").  For every row i of d_H[N x dim] keeps the k largest
+ * entries by signed value; ties at the k-th value go to the lower column, so
+ * exactly k survive.  d_sp_index[i,0..k) = kept columns in ascending order,
+ * d_sp_data[i,t] = H[i, sp_index[i,t]] (identical bits).  -0.0 and +0.0 compare
+ * equal; NaN is outside the contract.
+ */
+MAXK_API maxk_status maxk_topk_cbsr(const float* d_H, int64_t N, int32_t dim, int32_t k, float* d_sp_data, void* d_sp_index,
+                           int32_t index_bytes, void* stream);
+
+/*
+ * Forward aggregation, row-wise-product SpGEMM with dense output (Eq. 2 left;
+ * Sec. 3.2; Alg. 1):  Y[i,:] = sum_{p in row i} val[p] * X[col[p],:], where X
+ * is the N x dim matrix the CBSR describes.  d_Y is fp32 [N x dim].  Entries of
+ * a CBSR row may come in any order; fp32 accumulation order is unspecified.
+ */
+MAXK_API maxk_status maxk_spgemm_fwd(maxk_graph* g, const float* d_sp_data, const void* d_sp_index, int32_t index_bytes,
+                            int32_t dim, int32_t k, float* d_Y, void* stream);
+
+/*
+ * Backward aggregation, sampled SSpMM (Eq. 2 right; Eq. 3; Alg. 2 with the
+ * destination read as the neighbour row):  for every stored entry (i,j) of A,
+ * dXs[j,t] += val * dY[i, sp_index[j,t]], i.e. dXs = (A^T dY) at each row's CBSR
+ * columns.  d_dY is fp32 [N x dim]; d_dXs is fp32 [N x k], laid out like sp_data.
+ */
+MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void* d_sp_index, int32_t index_bytes,
+                           int32_t dim, int32_t k, float* d_dXs, void* stream);
+
+/*
+ * Dense-feature SpMM Y = A * H on the same graph handle: the operator the paper
+ * measures its speedups against (Sec. 5.2), here as a same-GPU baseline.
+ */
+MAXK_API maxk_status spmm_baseline(maxk_graph* g, const float* d_H, int32_t dim, float* d_Y, void* stream);
+
+/* Text for a status code (static storage). */
+MAXK_API const char* maxk_status_string(maxk_status s);
+
+/* hipError_t (as int) of the last HIP failure seen by this thread, 0 if none. */
+MAXK_API int32_t maxk_last_hip_error(void);
+
+/* Library version, MAJOR*10000 + MINOR*100 + PATCH. */
+MAXK_API int32_t maxk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAXK_H */

@@ -1,0 +1,85 @@
+// Internal declarations shared by the translation units of libmaxk (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/maxk.h"
+
+namespace maxk {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+// One unit of scheduled work: a contiguous run of stored entries of one row
+// (forward / push backward / dense SpMM) or of one column of A^T (pull backward).
+// The paper's "edge group" (Sec. 4.1), sized for a 64-wide wavefront.
+struct WorkItem {
+    int32_t row;    // output row (or destination node for the CSC lists)
+    int32_t begin;  // first stored entry
+    int32_t end;    // one past the last
+    int32_t slot;   // -1: this item owns the whole row and writes the result; else partial-sum slot
+};
+
+// A row whose entries were split over several items; its partial sums live in
+// slots [slot_begin, slot_begin + slot_count) and are added up by a second kernel.
+struct SplitRow {
+    int32_t row;
+    int32_t slot_begin;
+    int32_t slot_count;
+};
+
+struct ItemList {
+    WorkItem* d_items = nullptr;
+    SplitRow* d_split = nullptr;
+    int64_t n_items = 0;
+    int64_t n_split = 0;
+    int64_t n_slots = 0;
+};
+
+extern thread_local int32_t g_last_hip_error;
+
+inline maxk_status hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int32_t)e;
+    (void)hipGetLastError();  // clear the sticky launch error, the code is kept above
+    return e == hipErrorOutOfMemory ? MAXK_OUT_OF_MEMORY : MAXK_HIP_ERROR;
+}
+
+#define MAXK_HIP_TRY(expr)                                   \
+    do {                                                     \
+        hipError_t _e = (expr);                              \
+        if (_e != hipSuccess) return ::maxk::hip_fail(_e);   \
+    } while (0)
+
+#define MAXK_LAUNCH_CHECK()                                  \
+    do {                                                     \
+        hipError_t _e = hipGetLastError();                   \
+        if (_e != hipSuccess) return ::maxk::hip_fail(_e);   \
+    } while (0)
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// ---- launchers implemented in the kernel files (device pointers throughout) ----
+
+maxk_status launch_topk(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
+                        hipStream_t s);
+
+maxk_status launch_spgemm_fwd(const ItemList& items, const int32_t* col, const float* val, const float* sp_data,
+                              const void* sp_index, int index_bytes, int dim, int k, float* Y, float* partials,
+                              hipStream_t s);
+
+maxk_status launch_spmm(const ItemList& items, const int32_t* col, const float* val, const float* H, int dim,
+                        float* Y, float* partials, hipStream_t s);
+
+maxk_status launch_bwd_pull(const ItemList& csc_items, const int32_t* csc_src, const float* csc_val, const float* dY,
+                            const void* sp_index, int index_bytes, int dim, int k, float* dXs, float* partials,
+                            hipStream_t s);
+
+maxk_status launch_bwd_push(const ItemList& items, const int32_t* col, const float* val, const float* dY,
+                            const void* sp_index, int index_bytes, int64_t N, int dim, int k, float* dXs,
+                            hipStream_t s);
+
+// out[row,:] = sum of the row's partial slots, for every split row (width = row length in floats)
+maxk_status launch_combine(const ItemList& items, const float* partials, int width, float* out, hipStream_t s);
+
+}  // namespace maxk

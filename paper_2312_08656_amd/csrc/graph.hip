@@ -1,0 +1,418 @@
+// Graph handle: load-time preprocessing of the adjacency (the paper's O(n)
+// partition of rows into edge groups "during graph loading", Sec. 4.1 / 4.2),
+// and the extern "C" entry points of the library.
+//
+// Preprocessing builds, once per graph:
+//   - the forward work-item list: rows cut into runs of at most `chunk` stored
+//     entries, ordered longest first so the heavy tail of a power-law degree
+//     distribution starts early and the short rows fill in behind it;
+//   - A^T as value-carrying CSC (stable radix sort of the entries by column, so
+//     in-entries of a node stay ordered by source row: deterministic sums) and
+//     its work-item list, for the pull backward kernel;
+//   - one partial-sum workspace shared by all kernels of the handle.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include <rocprim/rocprim.hpp>
+
+#include "common.hpp"
+
+struct maxk_graph {
+    int64_t N = 0, nnz = 0;
+    const int32_t* d_rowptr = nullptr;  // caller's CSR, aliased
+    const int32_t* d_col = nullptr;
+    const float* d_val = nullptr;
+    maxk::ItemList csr_items;  // over rows of A
+    maxk::ItemList csc_items;  // over columns of A (rows of A^T)
+    int32_t* d_csc_ptr = nullptr;
+    int32_t* d_csc_src = nullptr;
+    float* d_csc_val = nullptr;
+    float* d_partials = nullptr;
+    int64_t partial_floats = 0;
+    int64_t max_degree = 0;
+    int32_t bwd_mode = MAXK_BWD_AUTO;
+    int32_t chunk = 0;
+    int device = 0;
+};
+
+namespace maxk {
+
+thread_local int32_t g_last_hip_error = 0;
+
+namespace {
+
+int env_int(const char* name, int dflt, int lo, int hi)
+{
+    const char* v = std::getenv(name);
+    if (!v || !*v) return dflt;
+    long x = std::strtol(v, nullptr, 10);
+    if (x < lo || x > hi) return dflt;
+    return (int)x;
+}
+
+// Host side of the partition: ptr[n+1] -> items (longest first) + split rows.
+void build_items(const std::vector<int32_t>& ptr, int64_t n, int chunk, std::vector<WorkItem>& items,
+                 std::vector<SplitRow>& split, int64_t& n_slots, int64_t& max_len)
+{
+    items.clear();
+    split.clear();
+    n_slots = 0;
+    max_len = 0;
+    items.reserve((size_t)n + 1024);
+    for (int64_t i = 0; i < n; ++i) {
+        const int32_t b = ptr[i], e = ptr[i + 1];
+        const int64_t len = (int64_t)e - b;
+        max_len = std::max(max_len, len);
+        if (len <= chunk) {
+            items.push_back(WorkItem{(int32_t)i, b, e, -1});
+        } else {
+            // equal-sized pieces, each at most `chunk`
+            const int64_t pieces = (len + chunk - 1) / chunk;
+            split.push_back(SplitRow{(int32_t)i, (int32_t)n_slots, (int32_t)pieces});
+            for (int64_t s = 0; s < pieces; ++s) {
+                const int32_t pb = (int32_t)(b + len * s / pieces), pe = (int32_t)(b + len * (s + 1) / pieces);
+                items.push_back(WorkItem{(int32_t)i, pb, pe, (int32_t)(n_slots + s)});
+            }
+            n_slots += pieces;
+        }
+    }
+    std::stable_sort(items.begin(), items.end(), [](const WorkItem& a, const WorkItem& b) {
+        return (a.end - a.begin) > (b.end - b.begin);
+    });
+}
+
+maxk_status upload_items(const std::vector<WorkItem>& items, const std::vector<SplitRow>& split, int64_t n_slots,
+                         ItemList& L, hipStream_t s)
+{
+    L.n_items = (int64_t)items.size();
+    L.n_split = (int64_t)split.size();
+    L.n_slots = n_slots;
+    if (L.n_items) {
+        MAXK_HIP_TRY(hipMalloc((void**)&L.d_items, sizeof(WorkItem) * items.size()));
+        MAXK_HIP_TRY(hipMemcpyAsync(L.d_items, items.data(), sizeof(WorkItem) * items.size(), hipMemcpyHostToDevice, s));
+    }
+    if (L.n_split) {
+        MAXK_HIP_TRY(hipMalloc((void**)&L.d_split, sizeof(SplitRow) * split.size()));
+        MAXK_HIP_TRY(hipMemcpyAsync(L.d_split, split.data(), sizeof(SplitRow) * split.size(), hipMemcpyHostToDevice, s));
+    }
+    MAXK_HIP_TRY(hipStreamSynchronize(s));  // the host vectors go out of scope after this
+    return MAXK_OK;
+}
+
+// row_of[p] = the row that stored entry p belongs to (binary search in rowptr)
+__global__ __launch_bounds__(256) void entry_rows_kernel(const int32_t* __restrict__ rowptr, int64_t N, int64_t nnz,
+                                                         int32_t* __restrict__ row_of, uint32_t* __restrict__ iota)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
+        int64_t lo = 0, hi = N;  // largest i with rowptr[i] <= p
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if ((int64_t)rowptr[mid] <= p) lo = mid; else hi = mid;
+        }
+        row_of[p] = (int32_t)lo;
+        iota[p] = (uint32_t)p;
+    }
+}
+
+// count[j] = stored entries in column j; ids outside [0,N) are tallied in count[N]
+__global__ __launch_bounds__(256) void column_histogram_kernel(const int32_t* __restrict__ col, int64_t N,
+                                                               int64_t nnz, int32_t* __restrict__ count)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
+        const int32_t c = col[p];
+        atomicAdd(&count[(c >= 0 && (int64_t)c < N) ? c : N], 1);
+    }
+}
+
+__global__ __launch_bounds__(256) void gather_transposed_kernel(const uint32_t* __restrict__ perm,
+                                                                const int32_t* __restrict__ row_of,
+                                                                const float* __restrict__ val, int64_t nnz,
+                                                                int32_t* __restrict__ csc_src,
+                                                                float* __restrict__ csc_val)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nnz; q += stride) {
+        const uint32_t p = perm[q];
+        csc_src[q] = row_of[p];
+        csc_val[q] = val[p];
+    }
+}
+
+// A^T in CSC: csc_ptr[N+1] (host copy returned), csc_src / csc_val on the device.
+maxk_status build_csc(maxk_graph* g, std::vector<int32_t>& h_csc_ptr, hipStream_t s)
+{
+    const int64_t N = g->N, nnz = g->nnz;
+    h_csc_ptr.assign((size_t)N + 1, 0);
+    MAXK_HIP_TRY(hipMalloc((void**)&g->d_csc_ptr, sizeof(int32_t) * (size_t)(N + 1)));
+    if (nnz == 0) {
+        MAXK_HIP_TRY(hipMemsetAsync(g->d_csc_ptr, 0, sizeof(int32_t) * (size_t)(N + 1), s));
+        MAXK_HIP_TRY(hipStreamSynchronize(s));
+        return MAXK_OK;
+    }
+    MAXK_HIP_TRY(hipMalloc((void**)&g->d_csc_src, sizeof(int32_t) * (size_t)nnz));
+    MAXK_HIP_TRY(hipMalloc((void**)&g->d_csc_val, sizeof(float) * (size_t)nnz));
+
+    int32_t *d_row_of = nullptr, *d_count = nullptr;
+    uint32_t *d_iota = nullptr, *d_perm = nullptr, *d_keys_out = nullptr;
+    void* d_tmp = nullptr;
+    maxk_status st = MAXK_OK;
+    auto cleanup = [&]() {
+        (void)hipFree(d_row_of); (void)hipFree(d_count); (void)hipFree(d_iota);
+        (void)hipFree(d_perm); (void)hipFree(d_keys_out); (void)hipFree(d_tmp);
+    };
+#define MAXK_TRY_CLEAN(expr)                        \
+    do {                                            \
+        hipError_t _e = (expr);                     \
+        if (_e != hipSuccess) { cleanup(); return hip_fail(_e); } \
+    } while (0)
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_row_of, sizeof(int32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_iota, sizeof(uint32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_perm, sizeof(uint32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_keys_out, sizeof(uint32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_count, sizeof(int32_t) * (size_t)(N + 1)));
+    MAXK_TRY_CLEAN(hipMemsetAsync(d_count, 0, sizeof(int32_t) * (size_t)(N + 1), s));
+
+    const unsigned blocks = (unsigned)std::min<int64_t>((nnz + 255) / 256, 65536);
+    hipLaunchKernelGGL(entry_rows_kernel, dim3(blocks), dim3(256), 0, s, g->d_rowptr, N, nnz, d_row_of, d_iota);
+    hipLaunchKernelGGL(column_histogram_kernel, dim3(blocks), dim3(256), 0, s, g->d_col, N, nnz, d_count);
+    MAXK_TRY_CLEAN(hipGetLastError());
+
+    // stable sort of entry ids by column: in-entries of a node keep ascending source row
+    int end_bit = 1;
+    while (end_bit < 32 && ((int64_t)1 << end_bit) < N) ++end_bit;
+    size_t tmp_bytes = 0;
+    const uint32_t* keys_in = reinterpret_cast<const uint32_t*>(g->d_col);
+    MAXK_TRY_CLEAN(rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys_in, d_keys_out, d_iota, d_perm, (size_t)nnz, 0,
+                                             (unsigned)end_bit, s));
+    MAXK_TRY_CLEAN(hipMalloc(&d_tmp, tmp_bytes ? tmp_bytes : 16));
+    MAXK_TRY_CLEAN(rocprim::radix_sort_pairs(d_tmp, tmp_bytes, keys_in, d_keys_out, d_iota, d_perm, (size_t)nnz, 0,
+                                             (unsigned)end_bit, s));
+    hipLaunchKernelGGL(gather_transposed_kernel, dim3(blocks), dim3(256), 0, s, d_perm, d_row_of, g->d_val, nnz,
+                       g->d_csc_src, g->d_csc_val);
+    MAXK_TRY_CLEAN(hipGetLastError());
+
+    // column counts -> pointers (host scan over N values)
+    std::vector<int32_t> h_count((size_t)N + 1);
+    MAXK_TRY_CLEAN(hipMemcpyAsync(h_count.data(), d_count, sizeof(int32_t) * (size_t)(N + 1), hipMemcpyDeviceToHost, s));
+    MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+    int64_t run = 0;
+    for (int64_t j = 0; j < N; ++j) {
+        h_csc_ptr[(size_t)j] = (int32_t)run;
+        run += h_count[(size_t)j];
+    }
+    h_csc_ptr[(size_t)N] = (int32_t)run;
+    if (run != nnz) st = MAXK_INVALID_ARGUMENT;  // a column id fell outside [0,N)
+    MAXK_TRY_CLEAN(hipMemcpyAsync(g->d_csc_ptr, h_csc_ptr.data(), sizeof(int32_t) * (size_t)(N + 1), hipMemcpyHostToDevice, s));
+    MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+#undef MAXK_TRY_CLEAN
+    cleanup();
+    return st;
+}
+
+maxk_status ensure_workspace(maxk_graph* g, int dim, int k)
+{
+    const int64_t need = std::max<int64_t>(g->csr_items.n_slots * (int64_t)dim, g->csc_items.n_slots * (int64_t)k);
+    if (need <= g->partial_floats) return MAXK_OK;
+    float* fresh = nullptr;
+    MAXK_HIP_TRY(hipMalloc((void**)&fresh, sizeof(float) * (size_t)need));
+    if (g->d_partials) {
+        MAXK_HIP_TRY(hipDeviceSynchronize());  // nothing may still be using the old buffer
+        (void)hipFree(g->d_partials);
+    }
+    g->d_partials = fresh;
+    g->partial_floats = need;
+    return MAXK_OK;
+}
+
+bool bad_index_bytes(int index_bytes, int dim)
+{
+    if (index_bytes == 1) return dim > 256;
+    if (index_bytes == 2) return dim > 65536;
+    return index_bytes != 4;
+}
+
+}  // namespace
+}  // namespace maxk
+
+using namespace maxk;
+
+extern "C" {
+
+MAXK_API maxk_status maxk_graph_create(maxk_graph** out, int64_t N, int64_t nnz, const int32_t* d_rowptr,
+                              const int32_t* d_colidx, const float* d_val, void* stream)
+{
+    if (!out) return MAXK_INVALID_ARGUMENT;
+    *out = nullptr;
+    if (N < 0 || nnz < 0 || N > 0x7FFFFFF0ll || nnz > 0x7FFFFFF0ll) return MAXK_INVALID_ARGUMENT;
+    if (!d_rowptr || (nnz > 0 && (!d_colidx || !d_val))) return MAXK_INVALID_ARGUMENT;
+    if (!aligned(d_rowptr, 4) || !aligned(d_colidx, 4) || !aligned(d_val, 4)) return MAXK_INVALID_ARGUMENT;
+    hipStream_t s = (hipStream_t)stream;
+
+    maxk_graph* g = new (std::nothrow) maxk_graph();
+    if (!g) return MAXK_OUT_OF_MEMORY;
+    g->N = N;
+    g->nnz = nnz;
+    g->d_rowptr = d_rowptr;
+    g->d_col = d_colidx;
+    g->d_val = d_val;
+    g->chunk = env_int("MAXK_CHUNK", 1024, 64, 1 << 20);
+    (void)hipGetDevice(&g->device);
+
+    maxk_status st = MAXK_OK;
+    try {
+        std::vector<int32_t> h_rowptr((size_t)N + 1);
+        hipError_t e = hipMemcpyAsync(h_rowptr.data(), d_rowptr, sizeof(int32_t) * (size_t)(N + 1), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) { st = hip_fail(e); goto fail; }
+        if (h_rowptr[0] != 0 || (int64_t)h_rowptr[(size_t)N] != nnz) { st = MAXK_INVALID_ARGUMENT; goto fail; }
+        for (int64_t i = 0; i < N; ++i)
+            if (h_rowptr[(size_t)i + 1] < h_rowptr[(size_t)i]) { st = MAXK_INVALID_ARGUMENT; goto fail; }
+
+        std::vector<WorkItem> items;
+        std::vector<SplitRow> split;
+        int64_t n_slots = 0, max_len = 0;
+        build_items(h_rowptr, N, g->chunk, items, split, n_slots, max_len);
+        g->max_degree = max_len;
+        st = upload_items(items, split, n_slots, g->csr_items, s);
+        if (st != MAXK_OK) goto fail;
+
+        std::vector<int32_t> h_csc_ptr;
+        st = build_csc(g, h_csc_ptr, s);
+        if (st != MAXK_OK) goto fail;
+        build_items(h_csc_ptr, N, g->chunk, items, split, n_slots, max_len);
+        st = upload_items(items, split, n_slots, g->csc_items, s);
+        if (st != MAXK_OK) goto fail;
+    } catch (const std::bad_alloc&) {
+        st = MAXK_OUT_OF_MEMORY;
+        goto fail;
+    }
+    *out = g;
+    return MAXK_OK;
+fail:
+    maxk_graph_destroy(g);
+    return st;
+}
+
+MAXK_API maxk_status maxk_graph_destroy(maxk_graph* g)
+{
+    if (!g) return MAXK_OK;
+    (void)hipFree(g->csr_items.d_items);
+    (void)hipFree(g->csr_items.d_split);
+    (void)hipFree(g->csc_items.d_items);
+    (void)hipFree(g->csc_items.d_split);
+    (void)hipFree(g->d_csc_ptr);
+    (void)hipFree(g->d_csc_src);
+    (void)hipFree(g->d_csc_val);
+    (void)hipFree(g->d_partials);
+    delete g;
+    return MAXK_OK;
+}
+
+MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k)
+{
+    if (!g || dim < 1 || k < 1 || k > dim) return MAXK_INVALID_ARGUMENT;
+    if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
+    return ensure_workspace(g, dim, k);
+}
+
+MAXK_API maxk_status maxk_graph_set_bwd_mode(maxk_graph* g, int32_t mode)
+{
+    if (!g || mode < MAXK_BWD_AUTO || mode > MAXK_BWD_PUSH_CSR) return MAXK_INVALID_ARGUMENT;
+    g->bwd_mode = mode;
+    return MAXK_OK;
+}
+
+MAXK_API maxk_status maxk_graph_info(const maxk_graph* g, int64_t* N, int64_t* nnz, int64_t* n_fwd_items, int64_t* n_split_rows,
+                            int64_t* max_degree, int64_t* workspace_bytes)
+{
+    if (!g) return MAXK_INVALID_ARGUMENT;
+    if (N) *N = g->N;
+    if (nnz) *nnz = g->nnz;
+    if (n_fwd_items) *n_fwd_items = g->csr_items.n_items;
+    if (n_split_rows) *n_split_rows = g->csr_items.n_split;
+    if (max_degree) *max_degree = g->max_degree;
+    if (workspace_bytes) *workspace_bytes = g->partial_floats * (int64_t)sizeof(float);
+    return MAXK_OK;
+}
+
+MAXK_API maxk_status maxk_topk_cbsr(const float* d_H, int64_t N, int32_t dim, int32_t k, float* d_sp_data, void* d_sp_index,
+                           int32_t index_bytes, void* stream)
+{
+    if (N < 0 || dim < 1 || k < 1 || k > dim || bad_index_bytes(index_bytes, dim)) return MAXK_INVALID_ARGUMENT;
+    if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
+    if (N > 0x7FFFFFF0ll) return MAXK_INVALID_ARGUMENT;
+    if (N == 0) return MAXK_OK;
+    if (!d_H || !d_sp_data || !d_sp_index) return MAXK_INVALID_ARGUMENT;
+    if (!aligned(d_H, 4) || !aligned(d_sp_data, 4) || !aligned(d_sp_index, (size_t)index_bytes))
+        return MAXK_INVALID_ARGUMENT;
+    return launch_topk(d_H, N, dim, k, d_sp_data, d_sp_index, index_bytes, (hipStream_t)stream);
+}
+
+MAXK_API maxk_status maxk_spgemm_fwd(maxk_graph* g, const float* d_sp_data, const void* d_sp_index, int32_t index_bytes,
+                            int32_t dim, int32_t k, float* d_Y, void* stream)
+{
+    if (!g || dim < 1 || k < 1 || k > dim || bad_index_bytes(index_bytes, dim)) return MAXK_INVALID_ARGUMENT;
+    if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
+    if (g->N == 0) return MAXK_OK;
+    if (!d_sp_data || !d_sp_index || !d_Y) return MAXK_INVALID_ARGUMENT;
+    if (!aligned(d_sp_data, 4) || !aligned(d_Y, 4) || !aligned(d_sp_index, (size_t)index_bytes))
+        return MAXK_INVALID_ARGUMENT;
+    maxk_status st = ensure_workspace(g, dim, k);
+    if (st != MAXK_OK) return st;
+    return launch_spgemm_fwd(g->csr_items, g->d_col, g->d_val, d_sp_data, d_sp_index, index_bytes, dim, k, d_Y,
+                             g->d_partials, (hipStream_t)stream);
+}
+
+MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void* d_sp_index, int32_t index_bytes, int32_t dim,
+                           int32_t k, float* d_dXs, void* stream)
+{
+    if (!g || dim < 1 || k < 1 || k > dim || bad_index_bytes(index_bytes, dim)) return MAXK_INVALID_ARGUMENT;
+    if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
+    if (g->N == 0) return MAXK_OK;
+    if (!d_dY || !d_sp_index || !d_dXs) return MAXK_INVALID_ARGUMENT;
+    if (!aligned(d_dY, 4) || !aligned(d_dXs, 4) || !aligned(d_sp_index, (size_t)index_bytes))
+        return MAXK_INVALID_ARGUMENT;
+    maxk_status st = ensure_workspace(g, dim, k);
+    if (st != MAXK_OK) return st;
+    int mode = g->bwd_mode;
+    if (mode == MAXK_BWD_AUTO) mode = MAXK_BWD_PUSH_CSR;
+    if (mode == MAXK_BWD_PULL_CSC)
+        return launch_bwd_pull(g->csc_items, g->d_csc_src, g->d_csc_val, d_dY, d_sp_index, index_bytes, dim, k, d_dXs,
+                               g->d_partials, (hipStream_t)stream);
+    return launch_bwd_push(g->csr_items, g->d_col, g->d_val, d_dY, d_sp_index, index_bytes, g->N, dim, k, d_dXs,
+                           (hipStream_t)stream);
+}
+
+MAXK_API maxk_status spmm_baseline(maxk_graph* g, const float* d_H, int32_t dim, float* d_Y, void* stream)
+{
+    if (!g || dim < 1) return MAXK_INVALID_ARGUMENT;
+    if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
+    if (g->N == 0) return MAXK_OK;
+    if (!d_H || !d_Y || !aligned(d_H, 4) || !aligned(d_Y, 4)) return MAXK_INVALID_ARGUMENT;
+    maxk_status st = ensure_workspace(g, dim, 1);
+    if (st != MAXK_OK) return st;
+    return launch_spmm(g->csr_items, g->d_col, g->d_val, d_H, dim, d_Y, g->d_partials, (hipStream_t)stream);
+}
+
+MAXK_API const char* maxk_status_string(maxk_status s)
+{
+    switch (s) {
+        case MAXK_OK: return "ok";
+        case MAXK_INVALID_ARGUMENT: return "invalid argument";
+        case MAXK_UNSUPPORTED: return "unsupported size";
+        case MAXK_HIP_ERROR: return "HIP runtime error";
+        case MAXK_OUT_OF_MEMORY: return "out of device or host memory";
+        default: return "unknown status";
+    }
+}
+
+MAXK_API int32_t maxk_last_hip_error(void) { return g_last_hip_error; }
+
+MAXK_API int32_t maxk_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,177 @@
+// MaxK selection + CBSR packing (Sec. 3.1 definition, Eq. 1; CBSR of Sec. 3.2).
+//
+// One 64-lane wavefront owns one row of H, held entirely in registers
+// (E values per lane).  The paper's kernel bisects a floating-point pivot
+// between min and max and stops after at most 10 rounds, which cannot separate
+// equal values at rank k.  Here the k-th largest value is found EXACTLY by a
+// most-significant-bit-first radix descent on order-preserving integer keys:
+// each step is E compares + E wave ballots + scalar popcounts, no LDS and no
+// barrier, and the descent stops early as soon as a prefix keeps exactly k
+// entries (the usual case for continuous data, after ~10 bits).  Ties at the
+// k-th value are resolved toward the lower column with ballot prefix counts,
+// and the same prefix counts give every survivor its slot in the CBSR row, so
+// indices come out ascending.
+#include "common.hpp"
+
+namespace maxk {
+namespace {
+
+__device__ __forceinline__ uint32_t order_key(float x)
+{
+    uint32_t b = __float_as_uint(x);
+    if ((b << 1) == 0u) b = 0u;  // -0.0 and +0.0 compare equal
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__device__ __forceinline__ int lanes_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Column of element e of lane l: chunks of 64*V columns, V consecutive per lane.
+template <int V>
+__device__ __forceinline__ int column_of(int lane, int e)
+{
+    return (e / V) * (kWave * V) + lane * V + (e % V);
+}
+
+// pos[e] = number of flagged elements that precede (lane, e) in column order
+template <int E, int V>
+__device__ __forceinline__ void column_order_prefix(const bool (&flag)[E], int (&pos)[E])
+{
+    int before_chunks = 0;
+#pragma unroll
+    for (int c = 0; c < E / V; ++c) {
+        int in_chunk_before_lane = 0, chunk_total = 0;
+        uint64_t m[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            m[v] = __builtin_amdgcn_ballot_w64(flag[c * V + v]);
+            in_chunk_before_lane += lanes_below(m[v]);
+            chunk_total += __builtin_popcountll(m[v]);
+        }
+        int own = 0;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            pos[c * V + v] = before_chunks + in_chunk_before_lane + own;
+            own += flag[c * V + v] ? 1 : 0;
+        }
+        before_chunks += chunk_total;
+    }
+}
+
+template <int E, int V, typename IdxT>
+__global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict__ H, int64_t N, int dim, int k,
+                                                        float* __restrict__ sp_data, IdxT* __restrict__ sp_index)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t row = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (row >= N) return;
+    const float* __restrict__ h = H + row * (int64_t)dim;
+
+    float v[E];
+    uint32_t key[E];
+#pragma unroll
+    for (int c = 0; c < E / V; ++c) {
+        const int base = c * (kWave * V) + lane * V;
+        if constexpr (V == 4) {
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            const bool in = base < dim;  // dim % 4 == 0 on this path
+            if (in) x = *reinterpret_cast<const float4*>(h + base);
+            v[c * 4 + 0] = x.x; v[c * 4 + 1] = x.y; v[c * 4 + 2] = x.z; v[c * 4 + 3] = x.w;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) key[c * 4 + j] = in ? order_key(v[c * 4 + j]) : 0u;
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const bool in = base + j < dim;
+                v[c * V + j] = in ? h[base + j] : 0.f;
+                key[c * V + j] = in ? order_key(v[c * V + j]) : 0u;  // 0 ranks below every non-NaN key
+            }
+        }
+    }
+
+    // k-th largest key by MSB-first descent; `exact` = the prefix already keeps exactly k
+    uint32_t prefix = 0u;
+    bool exact = false;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = prefix | (1u << bit);
+        int cnt = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= cand));
+        if (cnt >= k) {
+            prefix = cand;
+            if (cnt == k) { exact = true; break; }
+        }
+    }
+
+    bool sel[E];
+    if (exact) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) sel[e] = key[e] >= prefix;
+    } else {
+        // prefix is the k-th largest key and more than k entries are >= it: take all
+        // strictly larger ones, then the leftmost (k - those) of the equal ones
+        bool eq[E];
+        int greater = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            eq[e] = key[e] == prefix;
+            greater += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] > prefix));
+        }
+        const int need = k - greater;
+        int rank[E];
+        column_order_prefix<E, V>(eq, rank);
+#pragma unroll
+        for (int e = 0; e < E; ++e) sel[e] = key[e] > prefix || (eq[e] && rank[e] < need);
+    }
+
+    int pos[E];
+    column_order_prefix<E, V>(sel, pos);
+    float* __restrict__ od = sp_data + row * (int64_t)k;
+    IdxT* __restrict__ oi = sp_index + row * (int64_t)k;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        if (sel[e]) {
+            od[pos[e]] = v[e];
+            oi[pos[e]] = (IdxT)column_of<V>(lane, e);
+        }
+    }
+}
+
+template <int E, int V>
+maxk_status launch_e(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
+                     hipStream_t s)
+{
+    const int rows_per_block = 4;
+    const int64_t blocks = (N + rows_per_block - 1) / rows_per_block;
+    if (blocks > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
+    dim3 grid((unsigned)blocks), block(rows_per_block * kWave);
+    switch (index_bytes) {
+        case 1: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, uint8_t>), grid, block, 0, s, H, N, dim, k, sp_data, (uint8_t*)sp_index); break;
+        case 2: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, uint16_t>), grid, block, 0, s, H, N, dim, k, sp_data, (uint16_t*)sp_index); break;
+        default: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, int32_t>), grid, block, 0, s, H, N, dim, k, sp_data, (int32_t*)sp_index); break;
+    }
+    MAXK_LAUNCH_CHECK();
+    return MAXK_OK;
+}
+
+}  // namespace
+
+maxk_status launch_topk(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
+                        hipStream_t s)
+{
+    if (N == 0) return MAXK_OK;
+    const bool vec = (dim % 4 == 0) && aligned(H, 16);
+    if (vec) {
+        if (dim <= 256) return launch_e<4, 4>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+        if (dim <= 512) return launch_e<8, 4>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+        return launch_e<16, 4>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+    }
+    if (dim <= 64) return launch_e<1, 1>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+    if (dim <= 256) return launch_e<4, 1>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+    if (dim <= 512) return launch_e<8, 1>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+    return launch_e<16, 1>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+}
+
+}  // namespace maxk

@@ -1,0 +1,183 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs -- element by element at sizes the oracle finishes in seconds, and on
+sampled outputs (plus size-independent properties) at the full benchmark sizes.
+Bars: sp_index / sp_data bit-exact; fp32 outputs within 1e-5 * sum|terms| + 1e-6."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from helpers import csr_from_coo, read_golden
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2312_08656_amd as maxk
+    from gpu_common import (DeviceGraph, check_backward, check_forward, check_spmm, check_topk, full_pass, gpu_topk,
+                            index_to_numpy, say, to_dev)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    maxk.load_library()  # fails loudly if libmaxk.so is missing: there is no fallback
+
+
+# ------------------------------------------------------------------ small, element by element
+
+
+def test_golden_example_on_gpu():
+    g = read_golden("fig5_fig6_shape_example.txt")
+    N, dim, k = (int(r[1]) for r in g["dims"])
+    rowptr, col, val = csr_from_coo(N, [(int(a), int(b), float(c)) for a, b, c in g["A_coo"]])
+    H = np.array(g["H"], dtype=np.float32)
+    dY = np.array(g["dY"], dtype=np.float32)
+    for ib in (1, 2, 4):
+        sp_data, sp_index = gpu_topk(to_dev(H), k, ib)
+        assert np.array_equal(index_to_numpy(sp_index), np.array(g["sp_index"], dtype=np.int32))
+        assert np.array_equal(sp_data.cpu().numpy().view(np.uint32), np.array(g["sp_data"], np.float32).view(np.uint32))
+        gr = maxk.maxk_graph_create(to_dev(rowptr), to_dev(col), to_dev(val))
+        Y = torch.empty((N, dim), device="cuda")
+        maxk.maxk_spgemm_fwd(gr, sp_data, sp_index, dim, Y)
+        assert np.array_equal(Y.cpu().numpy(), np.array(g["Y"], dtype=np.float32))  # small integers: exact
+        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR):
+            gr.set_bwd_mode(mode)
+            dXs = torch.empty((N, k), device="cuda")
+            maxk.maxk_sspmm_bwd(gr, to_dev(dY), sp_index, dXs)
+            assert np.array_equal(dXs.cpu().numpy(), np.array(g["dXs"], dtype=np.float32))
+        gr.destroy()
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_directed"])
+def test_tiny_configs_full_compare(name):
+    cfg = synth.CONFIGS[name]
+    dg = DeviceGraph(synth.graph(name))
+    H, dY = synth.features(name, "H"), synth.features(name, "dY")
+    for k in (8, 1, 3, 64, 20):
+        say(f"  {name} k={k}")
+        full_pass(dg, H, dY, k, 1, sampled=False)
+    full_pass(dg, H, dY, 8, 4, sampled=False)
+    dg.close()
+
+
+@pytest.mark.parametrize("dim,k,ib", [(6, 3, 1), (37, 5, 1), (100, 100, 2), (256, 255, 1), (384, 96, 2), (512, 7, 4),
+                                       (1024, 128, 2), (64, 64, 1), (130, 33, 1)])
+def test_odd_shapes_and_index_widths(dim, k, ib):
+    # signed general weights on a directed graph: exercises the transpose and cancellation
+    g = synth.make_graph(700, 9000, 10, (0.5, 0.2, 0.2), directed=True, self_loops=False, seed=dim + k,
+                         weights="normal")
+    dg = DeviceGraph(g)
+    H, dY = synth.normal_matrix(g.N, dim, 3), synth.normal_matrix(g.N, dim, 4)
+    full_pass(dg, H, dY, k, ib, sampled=False)
+    dg.close()
+
+
+def test_topk_ties_signed_zero_and_infinities():
+    H = synth.normal_matrix(5000, 384, seed=5)
+    synth.add_tie_rows(H, seed=5, percent=40, pool=16, const_every=8)
+    H[7, :10] = [-0.0, 0.0, -0.0, 0.0, np.inf, -np.inf, np.inf, 0.0, -0.0, 1.0]
+    H[8, :] = -np.inf
+    H[9, :] = np.float32(-0.0)
+    H[9, 5] = 0.0
+    Hd = to_dev(H)
+    for k in (1, 2, 32, 96, 192, 383, 384):
+        sp_data, sp_index = gpu_topk(Hd, k, 2)
+        check_topk(H, k, sp_data, sp_index)
+    H256 = np.ascontiguousarray(H[:, :256])
+    for k in (31, 32, 128, 256):
+        sp_data, sp_index = gpu_topk(to_dev(H256), k, 1)
+        check_topk(H256, k, sp_data, sp_index)
+
+
+def test_empty_graph_empty_rows_duplicates_unsorted_columns():
+    # N == 0
+    z32 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    g0 = maxk.maxk_graph_create(z32, torch.empty(0, dtype=torch.int32, device="cuda"), torch.empty(0, device="cuda"))
+    maxk.maxk_spgemm_fwd(g0, torch.empty((0, 4), device="cuda"), torch.empty((0, 4), dtype=torch.uint8, device="cuda"),
+                         8, torch.empty((0, 8), device="cuda"))
+    g0.destroy()
+    maxk.maxk_topk_cbsr(torch.empty((0, 8), device="cuda"), 4, torch.empty((0, 4), device="cuda"),
+                        torch.empty((0, 4), dtype=torch.uint8, device="cuda"))
+    # a graph with no entries at all: outputs must be overwritten with zeros
+    N, dim, k = 50, 16, 4
+    H, dY = synth.normal_matrix(N, dim, 1), synth.normal_matrix(N, dim, 2)
+    ge = synth.Graph(N, np.zeros(N + 1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    dg = DeviceGraph(ge)
+    full_pass(dg, H, dY, k, 1, sampled=False)
+    dg.close()
+    # empty rows, empty columns, duplicate entries, columns in descending order within rows
+    rng = np.random.default_rng(3)
+    triples = []
+    for i in range(N):
+        if i % 5 == 0:
+            continue  # empty row
+        cols = rng.integers(0, N - 7, size=rng.integers(1, 200))  # last columns never referenced; repeats likely
+        triples += [(i, int(c), float(rng.standard_normal())) for c in cols]
+    rowptr, col, val = csr_from_coo(N, triples)
+    for i in range(N):  # reverse each row: unsorted columns
+        col[rowptr[i]:rowptr[i + 1]] = col[rowptr[i]:rowptr[i + 1]][::-1].copy()
+        val[rowptr[i]:rowptr[i + 1]] = val[rowptr[i]:rowptr[i + 1]][::-1].copy()
+    dg = DeviceGraph(synth.Graph(N, rowptr, col, val))
+    full_pass(dg, H, dY, k, 1, sampled=False)
+    dg.close()
+
+
+def test_misaligned_views_take_the_scalar_paths():
+    g = synth.graph("tiny_directed")
+    dim, k = 64, 8
+    H, dY = synth.features("tiny_directed", "H"), synth.features("tiny_directed", "dY")
+    dg = DeviceGraph(g)
+    ref = oracle.topk_cbsr(H, k)
+    # H, sp_data and sp_index each start 4 (resp. 1) bytes off a 16-byte boundary
+    Hbuf = torch.empty(g.N * dim + 1, device="cuda")
+    Hd = Hbuf[1:].view(g.N, dim)
+    Hd.copy_(to_dev(H))
+    dbuf = torch.empty(g.N * k + 1, device="cuda")
+    ibuf = torch.empty(g.N * k + 1, dtype=torch.uint8, device="cuda")
+    sp_data, sp_index = dbuf[1:].view(g.N, k), ibuf[1:].view(g.N, k)
+    maxk.maxk_topk_cbsr(Hd, k, sp_data, sp_index)
+    check_topk(H, k, sp_data, sp_index, ref)
+    check_forward(dg, ref, sp_data, sp_index, dim)
+    check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_PUSH_CSR)
+    check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_PULL_CSC)
+    check_spmm(dg, H, Hd)
+    dg.close()
+
+
+def test_outputs_are_overwritten_and_calls_repeat():
+    g = synth.graph("tiny")
+    dg = DeviceGraph(g)
+    H, dY = synth.features("tiny", "H"), synth.features("tiny", "dY")
+    Hd, dYd = to_dev(H), to_dev(dY)
+    sp_data, sp_index = gpu_topk(Hd, 8, 1)
+    Y1 = torch.full((g.N, 64), 123.0, device="cuda")
+    maxk.maxk_spgemm_fwd(dg.handle, sp_data, sp_index, 64, Y1)
+    ref, refabs = oracle.spgemm_fwd(g.rowptr, g.col, g.val, *oracle.topk_cbsr(H, 8), 64)
+    assert np.abs(Y1.cpu().numpy() - ref).max() < 1e-4
+    for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR):
+        dg.handle.set_bwd_mode(mode)
+        a = torch.full((g.N, 8), 55.0, device="cuda")
+        b = torch.full((g.N, 8), -7.0, device="cuda")
+        maxk.maxk_sspmm_bwd(dg.handle, dYd, sp_index, a)
+        maxk.maxk_sspmm_bwd(dg.handle, dYd, sp_index, b)
+        assert (a - b).abs().max().item() < 1e-5
+    dg.close()
+
+
+# ------------------------------------------------------------------ mid size, element by element
+
+
+def test_sparse_mid_full_compare():
+    name = "sparse_mid"
+    cfg = synth.CONFIGS[name]
+    g = synth.graph(name)
+    say(f"  {name}: {g.meta}")
+    dg = DeviceGraph(g)
+    say(f"  handle: {dg.handle.info()}")
+    H, dY = synth.features(name, "H"), synth.features(name, "dY")
+    for k in cfg.ks:
+        say(f"  {name} k={k}")
+        full_pass(dg, H, dY, k, cfg.index_bytes, sampled=False, spmm=(k == cfg.ks[0]))
+    dg.close()

@@ -1,0 +1,75 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times:
+CBSR compared bit-exactly on every row; forward / backward / dense SpMM compared on
+sampled outputs the oracle computes one by one (hub rows, rows at the chunk boundaries,
+random rows), plus the adjoint identity over the whole output."""
+import pytest
+import torch
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2312_08656_amd as maxk
+    from gpu_common import DeviceGraph, full_pass, say
+
+_cache = {}
+
+
+def _setup(name):
+    if name not in _cache:
+        _cache.clear()  # one big configuration resident at a time
+        g = synth.graph(name)
+        say(f"  {name}: {g.meta}")
+        dg = DeviceGraph(g)
+        say(f"  handle: {dg.handle.info()}")
+        _cache[name] = (dg, synth.features(name, "H"), synth.features(name, "dY"))
+    return _cache[name]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    maxk.load_library()
+    yield
+    for dg, _, _ in _cache.values():
+        dg.close()
+    _cache.clear()
+
+
+def test_dense_graph_builds():
+    dg, H, dY = _setup("dense")
+    info = dg.handle.info()
+    assert info["nnz"] == synth.CONFIGS["dense"].nnz == 114_848_855
+    assert 15_000 <= info["max_degree"] <= 25_000
+
+
+@pytest.mark.parametrize("k", synth.CONFIGS["dense"].ks)
+def test_dense_sampled(k):
+    dg, H, dY = _setup("dense")
+    say(f"  dense k={k}")
+    full_pass(dg, H, dY, k, 1, sampled=True, seed=k, n_random=600, spmm=(k == 32))
+
+
+def test_wide_hidden_graph_builds():
+    dg, H, dY = _setup("wide_hidden")
+    assert dg.handle.info()["nnz"] == 14_671_666
+
+
+@pytest.mark.parametrize("k", synth.CONFIGS["wide_hidden"].ks)
+def test_wide_hidden_sampled(k):
+    dg, H, dY = _setup("wide_hidden")
+    say(f"  wide_hidden k={k}")
+    full_pass(dg, H, dY, k, 2, sampled=True, seed=k, n_random=1500, spmm=(k == 32))
+
+
+def test_large_sparse_graph_builds():
+    dg, H, dY = _setup("large_sparse")
+    assert dg.handle.info()["nnz"] == 126_167_309
+
+
+def test_large_sparse_sampled():
+    dg, H, dY = _setup("large_sparse")
+    say("  large_sparse k=64")
+    full_pass(dg, H, dY, 64, 1, sampled=True, seed=64, n_random=1500, spmm=True)
