@@ -3,16 +3,25 @@
 //
 // One 64-lane wavefront (= one workgroup, so no cross-wave barrier exists)
 // owns one work item: a run of at most `chunk` stored entries of one row of A.
-// It keeps the dense output row (dim floats) in LDS, streams the item's
-// (col, val) pairs 64 at a time into registers with one coalesced load each,
-// and walks a FLAT list of units (entry, quad) -- unit u belongs to entry
-// u / (k/4) and covers CBSR positions 4*(u % (k/4)) .. +3 -- so all 64 lanes
-// stay busy for every k that is a multiple of 4: each lane fetches one float4
-// of sp_data and its 4 indices with one load each, U rounds in flight before
-// the first LDS update.  The scatter-add into the row buffer is ds_add_f32.
+// The item's (col, val) pairs are staged 64 at a time through LDS, and the
+// wavefront walks a FLAT list of units (entry e, position t): unit u belongs to
+// entry u / k and CBSR position u % k, so all 64 lanes stay busy for every k and
+// the k lanes of one entry read k contiguous values and k contiguous indices.
+//
+// Accumulation.  LDS floating-point atomics (ds_add_f32) retire about one lane
+// every three clocks on this chip (measured: ~190 clocks per wave instruction),
+// which capped the first version of this kernel at ~200 G updates/s no matter
+// the memory system.  A plain LDS read-add-write pair is ~14x faster, and it is
+// safe here without atomics because (a) the k positions of one CBSR row are
+// distinct columns, and (b) the entries that share one wave instruction (at most
+// NB = ceil(64/k)+1 consecutive ones) accumulate into NB PRIVATE copies of the
+// output row (copy e % NB), while LDS operations of one wavefront execute in
+// program order.  The copies are added up when the row is written out.
 // Rows longer than `chunk` write partial rows that a second kernel adds up
 // (deterministic order, and it bounds the length of any fp32 running sum);
 // every other row is written once, straight from LDS, fully coalesced.
+// Shapes whose private copies would not fit comfortably in LDS (tiny k with a
+// very wide row) fall back to the single-copy kernel with LDS atomics.
 #include "common.hpp"
 
 namespace maxk {
@@ -126,6 +135,85 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_kernel(const WorkItem* __res
     }
 }
 
+// Private output-row copies needed so that entries sharing a wave instruction never collide.
+__host__ __device__ constexpr int private_copies(int k)
+{
+    return (k >= kWave) ? ((k % kWave == 0) ? 1 : 2) : ((kWave % k == 0) ? kWave / k : (kWave - 1) / k + 2);
+}
+
+// K: MaxK k when known at compile time (0 = runtime); ROUNDS: 64-unit rounds in flight
+template <int K, int ROUNDS, typename IdxT>
+__global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* __restrict__ items,
+                                                               const int32_t* __restrict__ col,
+                                                               const float* __restrict__ val,
+                                                               const float* __restrict__ sp_data,
+                                                               const IdxT* __restrict__ sp_index, int dim, int k_rt,
+                                                               int nb_rt, float* __restrict__ Y,
+                                                               float* __restrict__ partials)
+{
+    extern __shared__ float lds[];
+    const int k = K ? K : k_rt;
+    const int nb = K ? private_copies(K) : nb_rt;
+    const int lane = threadIdx.x;
+    float* __restrict__ row_buf = lds;                                         // nb copies of the output row
+    int2* __restrict__ entry_buf = reinterpret_cast<int2*>(lds + ((nb * dim + 1) & ~1));  // 64 staged (col, val)
+    const WorkItem it = items[blockIdx.x];
+    for (int c = lane; c < nb * dim; c += kWave) row_buf[c] = 0.f;
+
+    for (int base = it.begin; base < it.end; base += kWave) {
+        const int n = min(kWave, it.end - base);
+        __syncthreads();  // previous batch fully consumed (and the zero fill done)
+        if (lane < n) entry_buf[lane] = make_int2(col[base + lane], __float_as_int(val[base + lane]));
+        __syncthreads();
+        const int units = n * k;
+        for (int u0 = 0; u0 < units; u0 += kWave * ROUNDS) {
+            float d[ROUNDS], a[ROUNDS];
+            int at[ROUNDS];
+            bool ok[ROUNDS];
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r) {
+                const int u = u0 + r * kWave + lane;
+                ok[r] = u < units;
+                const int uc = ok[r] ? u : 0;
+                const int e = uc / k;
+                const int t = uc - e * k;
+                const int2 ed = entry_buf[e];
+                a[r] = __int_as_float(ed.y);
+                const int64_t off = (int64_t)ed.x * k + t;
+                d[r] = sp_data[off];
+                at[r] = (e % nb) * dim + (int)sp_index[off];
+            }
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r) {
+                if (ok[r]) {
+                    const float old = row_buf[at[r]];
+                    row_buf[at[r]] = old + a[r] * d[r];
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    float* __restrict__ out = (it.slot < 0) ? Y + (int64_t)it.row * dim : partials + (int64_t)it.slot * dim;
+    if ((dim & 3) == 0) {
+        for (int c = lane * 4; c < dim; c += kWave * 4) {
+            float4 acc = *reinterpret_cast<const float4*>(row_buf + c);
+            for (int b = 1; b < nb; ++b) {
+                const float4 x = *reinterpret_cast<const float4*>(row_buf + b * dim + c);
+                acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+            }
+            *reinterpret_cast<float4*>(out + c) = acc;
+        }
+    } else {
+        for (int c = lane; c < dim; c += kWave) {
+            float acc = row_buf[c];
+            for (int b = 1; b < nb; ++b) acc += row_buf[b * dim + c];
+            out[c] = acc;
+        }
+    }
+}
+
+
 // out[row, c] = sum over the row's partial slots
 __global__ __launch_bounds__(256) void combine_kernel(const SplitRow* __restrict__ split, int64_t n_split,
                                                       const float* __restrict__ partials, int width,
@@ -153,21 +241,36 @@ maxk_status launch_ku(const ItemList& L, const int32_t* col, const float* val, c
 #define MAXK_FWD_CASE(KU)                                                                                          \
     hipLaunchKernelGGL((spgemm_fwd_kernel<VEC, KU, IdxT>), grid, block, lds, s, L.d_items, col, val, sp_data,      \
                        sp_index, dim, k, ku, Y, partials)
-    if (VEC == 4) {
-        switch (ku) {
-            case 2: MAXK_FWD_CASE(2); break;
-            case 4: MAXK_FWD_CASE(4); break;
-            case 8: MAXK_FWD_CASE(8); break;
-            case 16: MAXK_FWD_CASE(16); break;
-            case 24: MAXK_FWD_CASE(24); break;
-            case 32: MAXK_FWD_CASE(32); break;
-            case 48: MAXK_FWD_CASE(48); break;
-            default: MAXK_FWD_CASE(0); break;
-        }
-    } else {
-        MAXK_FWD_CASE(0);
-    }
+    MAXK_FWD_CASE(0);
 #undef MAXK_FWD_CASE
+    MAXK_LAUNCH_CHECK();
+    return MAXK_OK;
+}
+
+constexpr size_t kMaxPrivateLds = 40 * 1024;  // above this the private copies cost too much occupancy
+
+template <typename IdxT>
+maxk_status launch_rmw(const ItemList& L, const int32_t* col, const float* val, const float* sp_data,
+                       const IdxT* sp_index, int dim, int k, float* Y, float* partials, hipStream_t s)
+{
+    if (L.n_items > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
+    dim3 grid((unsigned)L.n_items), block(kWave);
+    const int nb = private_copies(k);
+    const size_t lds = sizeof(float) * (size_t)((nb * dim + 1) & ~1) + sizeof(int2) * kWave;
+#define MAXK_FWD_RMW(K, R)                                                                                        \
+    hipLaunchKernelGGL((spgemm_fwd_rmw_kernel<K, R, IdxT>), grid, block, lds, s, L.d_items, col, val, sp_data,    \
+                       sp_index, dim, k, nb, Y, partials)
+    switch (k) {
+        case 8: MAXK_FWD_RMW(8, 8); break;
+        case 16: MAXK_FWD_RMW(16, 8); break;
+        case 32: MAXK_FWD_RMW(32, 8); break;
+        case 64: MAXK_FWD_RMW(64, 8); break;
+        case 96: MAXK_FWD_RMW(96, 8); break;
+        case 128: MAXK_FWD_RMW(128, 8); break;
+        case 192: MAXK_FWD_RMW(192, 8); break;
+        default: MAXK_FWD_RMW(0, 8); break;
+    }
+#undef MAXK_FWD_RMW
     MAXK_LAUNCH_CHECK();
     return MAXK_OK;
 }
@@ -189,12 +292,12 @@ maxk_status launch_spgemm_fwd(const ItemList& L, const int32_t* col, const float
                               hipStream_t s)
 {
     if (L.n_items == 0) return MAXK_OK;
-    const bool vec = (k % 4 == 0) && aligned(sp_data, 16) && aligned(sp_index, (size_t)(4 * index_bytes));
     maxk_status st;
-    if (vec) {
-        if (index_bytes == 1) st = launch_ku<4>(L, col, val, sp_data, (const uint8_t*)sp_index, dim, k, Y, partials, s);
-        else if (index_bytes == 2) st = launch_ku<4>(L, col, val, sp_data, (const uint16_t*)sp_index, dim, k, Y, partials, s);
-        else st = launch_ku<4>(L, col, val, sp_data, (const int32_t*)sp_index, dim, k, Y, partials, s);
+    const size_t private_lds = sizeof(float) * (size_t)private_copies(k) * (size_t)dim;
+    if (private_lds <= kMaxPrivateLds) {
+        if (index_bytes == 1) st = launch_rmw(L, col, val, sp_data, (const uint8_t*)sp_index, dim, k, Y, partials, s);
+        else if (index_bytes == 2) st = launch_rmw(L, col, val, sp_data, (const uint16_t*)sp_index, dim, k, Y, partials, s);
+        else st = launch_rmw(L, col, val, sp_data, (const int32_t*)sp_index, dim, k, Y, partials, s);
     } else {
         if (index_bytes == 1) st = launch_ku<1>(L, col, val, sp_data, (const uint8_t*)sp_index, dim, k, Y, partials, s);
         else if (index_bytes == 2) st = launch_ku<1>(L, col, val, sp_data, (const uint16_t*)sp_index, dim, k, Y, partials, s);
