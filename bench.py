@@ -188,9 +188,10 @@ def main() -> int:
             row = {"k": k, "topk_ms": round(tk, 4), "fwd_ms": round(tf, 4), "fwd_ms_median": round(tf_med, 4),
                    "fwd_edges_k_per_s": nnz * k / (tf * 1e-3), "fwd_hbm_frac": round(b["fwd"] / (tf * 1e-3) / 8e12, 4),
                    "fwd_speedup_vs_spmm": round(spmm_ms / tf, 2)}
-            for mode, tag in ((maxk.BWD_PUSH_CSR, "bwd_push"), (maxk.BWD_PULL_CSC, "bwd_pull")):
+            for mode, tag in ((maxk.BWD_PUSH_CSR, "bwd_push"), (maxk.BWD_PULL_CSC, "bwd_pull"),
+                              (maxk.BWD_EXPAND_REDUCE, "bwd_expand_reduce")):
                 gr.set_bwd_mode(mode)
-                reps = args.sweep_reps if mode == maxk.BWD_PUSH_CSR else max(3, args.sweep_reps // 4)
+                reps = max(3, args.sweep_reps // 4)
                 tb, tb_med = timeit(lambda: maxk.maxk_sspmm_bwd(gr, dYd, si, dx), reps, warm=1)
                 row.update({f"{tag}_ms": round(tb, 4), f"{tag}_edges_k_per_s": nnz * k / (tb * 1e-3),
                             f"{tag}_hbm_frac": round(b["bwd"] / (tb * 1e-3) / 8e12, 4),

@@ -57,7 +57,9 @@ enum {
 enum {
     MAXK_BWD_AUTO = 0,    /* library's choice (the faster one on MI355X) */
     MAXK_BWD_PULL_CSC = 1,/* owner-computes over A^T stored as CSC: deterministic, no atomics */
-    MAXK_BWD_PUSH_CSR = 2 /* Alg. 2's dataflow: stage dY[i,:] on chip, push along row i of A with fp32 atomics */
+    MAXK_BWD_PUSH_CSR = 2,/* Alg. 2's dataflow: stage dY[i,:] on chip, push along row i of A with fp32 atomics */
+    MAXK_BWD_EXPAND_REDUCE = 3 /* Alg. 2's staging without atomics: write each entry's k products to a per-graph
+                                  buffer (nnz*k floats, sequential), then sum them per destination node */
 };
 
 typedef struct maxk_graph maxk_graph;
@@ -79,9 +81,10 @@ MAXK_API maxk_status maxk_graph_create(maxk_graph** out, int64_t N, int64_t nnz,
 MAXK_API maxk_status maxk_graph_destroy(maxk_graph* g);
 
 /*
- * Pre-allocates the handle's partial-sum workspace for hidden width `dim` and
- * MaxK `k`, so that later compute calls with dim' <= dim, k' <= k allocate
- * nothing.  Without it, the first compute call needing a larger workspace grows
+ * Pre-allocates the handle's workspaces (partial sums of split rows; the nnz*k
+ * float buffer of the expand/reduce backward kernel when that kernel would be
+ * used) for hidden width `dim` and MaxK `k`, so that later compute calls with
+ * dim' <= dim, k' <= k allocate nothing.  Without it, the first compute call needing a larger workspace grows
  * it (one synchronous allocation), later ones reuse it.
  */
 MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k);

@@ -8,6 +8,7 @@ is missing or a call fails, an exception is raised.
 """
 from .binding import (  # noqa: F401
     BWD_AUTO,
+    BWD_EXPAND_REDUCE,
     BWD_PULL_CSC,
     BWD_PUSH_CSR,
     MaxKError,

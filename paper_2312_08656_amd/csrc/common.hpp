@@ -79,6 +79,11 @@ maxk_status launch_bwd_push(const ItemList& items, const int32_t* col, const flo
                             const void* sp_index, int index_bytes, int64_t N, int dim, int k, float* dXs,
                             hipStream_t s);
 
+maxk_status launch_bwd_expand_reduce(const ItemList& csr_items, const int32_t* col, const float* val,
+                                     const ItemList& csc_items, const uint32_t* csc_entry, const float* dY,
+                                     const void* sp_index, int index_bytes, int dim, int k, float* expand,
+                                     float* dXs, float* partials, hipStream_t s);
+
 // out[row,:] = sum of the row's partial slots, for every split row (width = row length in floats)
 maxk_status launch_combine(const ItemList& items, const float* partials, int width, float* out, hipStream_t s);
 

@@ -11,6 +11,7 @@
 //     its work-item list, for the pull backward kernel;
 //   - one partial-sum workspace shared by all kernels of the handle.
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -30,8 +31,11 @@ struct maxk_graph {
     int32_t* d_csc_ptr = nullptr;
     int32_t* d_csc_src = nullptr;
     float* d_csc_val = nullptr;
+    uint32_t* d_csc_entry = nullptr;  // CSR entry id of every CSC position (the transposing permutation)
     float* d_partials = nullptr;
     int64_t partial_floats = 0;
+    float* d_expand = nullptr;  // per-entry contributions of the expand/reduce backward kernel (nnz * k floats)
+    int64_t expand_floats = 0;
     int64_t max_degree = 0;
     int32_t bwd_mode = MAXK_BWD_AUTO;
     int32_t chunk = 0;
@@ -158,12 +162,14 @@ maxk_status build_csc(maxk_graph* g, std::vector<int32_t>& h_csc_ptr, hipStream_
     MAXK_HIP_TRY(hipMalloc((void**)&g->d_csc_val, sizeof(float) * (size_t)nnz));
 
     int32_t *d_row_of = nullptr, *d_count = nullptr;
-    uint32_t *d_iota = nullptr, *d_perm = nullptr, *d_keys_out = nullptr;
+    uint32_t *d_iota = nullptr, *d_keys_out = nullptr;
+    MAXK_HIP_TRY(hipMalloc((void**)&g->d_csc_entry, sizeof(uint32_t) * (size_t)nnz));
+    uint32_t* d_perm = g->d_csc_entry;  // kept: the reduce phase of the backward pass gathers through it
     void* d_tmp = nullptr;
     maxk_status st = MAXK_OK;
     auto cleanup = [&]() {
         (void)hipFree(d_row_of); (void)hipFree(d_count); (void)hipFree(d_iota);
-        (void)hipFree(d_perm); (void)hipFree(d_keys_out); (void)hipFree(d_tmp);
+        (void)hipFree(d_keys_out); (void)hipFree(d_tmp);
     };
 #define MAXK_TRY_CLEAN(expr)                        \
     do {                                            \
@@ -172,7 +178,6 @@ maxk_status build_csc(maxk_graph* g, std::vector<int32_t>& h_csc_ptr, hipStream_
     } while (0)
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_row_of, sizeof(int32_t) * (size_t)nnz));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_iota, sizeof(uint32_t) * (size_t)nnz));
-    MAXK_TRY_CLEAN(hipMalloc((void**)&d_perm, sizeof(uint32_t) * (size_t)nnz));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_keys_out, sizeof(uint32_t) * (size_t)nnz));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_count, sizeof(int32_t) * (size_t)(N + 1)));
     MAXK_TRY_CLEAN(hipMemsetAsync(d_count, 0, sizeof(int32_t) * (size_t)(N + 1), s));
@@ -227,6 +232,33 @@ maxk_status ensure_workspace(maxk_graph* g, int dim, int k)
     g->d_partials = fresh;
     g->partial_floats = need;
     return MAXK_OK;
+}
+
+maxk_status ensure_expand(maxk_graph* g, int k)
+{
+    const int64_t need = g->nnz * (int64_t)k;
+    if (need <= g->expand_floats) return MAXK_OK;
+    float* fresh = nullptr;
+    MAXK_HIP_TRY(hipMalloc((void**)&fresh, sizeof(float) * (size_t)need));
+    if (g->d_expand) {
+        MAXK_HIP_TRY(hipDeviceSynchronize());
+        (void)hipFree(g->d_expand);
+    }
+    g->d_expand = fresh;
+    g->expand_floats = need;
+    return MAXK_OK;
+}
+
+// Backward kernel choice when the caller leaves it to the library.  Expand/reduce moves
+// 8k bytes per stored entry through HBM, pull touches about min(k, dim/32) cache lines of a
+// dY row per entry whatever k is, so pull wins once k is a large share of dim.
+int auto_bwd_mode(const maxk_graph* g, int dim, int k)
+{
+    const double lines = (dim / 32.0) * (1.0 - std::pow(1.0 - 32.0 / dim, (double)k));  // expected lines touched
+    const double pull_cost = (dim <= 32 ? 1.0 : lines) * 128.0 / 8.5;                  // bytes / (TB/s), measured rates
+    const double expand_cost = 8.0 * k / 4.3;
+    const bool fits = (double)g->nnz * k * 4.0 <= 96e9;
+    return (fits && expand_cost < pull_cost) ? MAXK_BWD_EXPAND_REDUCE : MAXK_BWD_PULL_CSC;
 }
 
 bool bad_index_bytes(int index_bytes, int dim)
@@ -308,6 +340,8 @@ MAXK_API maxk_status maxk_graph_destroy(maxk_graph* g)
     (void)hipFree(g->d_csc_ptr);
     (void)hipFree(g->d_csc_src);
     (void)hipFree(g->d_csc_val);
+    (void)hipFree(g->d_csc_entry);
+    (void)hipFree(g->d_expand);
     (void)hipFree(g->d_partials);
     delete g;
     return MAXK_OK;
@@ -317,12 +351,15 @@ MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k)
 {
     if (!g || dim < 1 || k < 1 || k > dim) return MAXK_INVALID_ARGUMENT;
     if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
-    return ensure_workspace(g, dim, k);
+    maxk_status st = ensure_workspace(g, dim, k);
+    if (st != MAXK_OK) return st;
+    const int mode = g->bwd_mode == MAXK_BWD_AUTO ? auto_bwd_mode(g, dim, k) : g->bwd_mode;
+    return mode == MAXK_BWD_EXPAND_REDUCE ? ensure_expand(g, k) : MAXK_OK;
 }
 
 MAXK_API maxk_status maxk_graph_set_bwd_mode(maxk_graph* g, int32_t mode)
 {
-    if (!g || mode < MAXK_BWD_AUTO || mode > MAXK_BWD_PUSH_CSR) return MAXK_INVALID_ARGUMENT;
+    if (!g || mode < MAXK_BWD_AUTO || mode > MAXK_BWD_EXPAND_REDUCE) return MAXK_INVALID_ARGUMENT;
     g->bwd_mode = mode;
     return MAXK_OK;
 }
@@ -336,7 +373,7 @@ MAXK_API maxk_status maxk_graph_info(const maxk_graph* g, int64_t* N, int64_t* n
     if (n_fwd_items) *n_fwd_items = g->csr_items.n_items;
     if (n_split_rows) *n_split_rows = g->csr_items.n_split;
     if (max_degree) *max_degree = g->max_degree;
-    if (workspace_bytes) *workspace_bytes = g->partial_floats * (int64_t)sizeof(float);
+    if (workspace_bytes) *workspace_bytes = (g->partial_floats + g->expand_floats) * (int64_t)sizeof(float);
     return MAXK_OK;
 }
 
@@ -380,7 +417,14 @@ MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void
     maxk_status st = ensure_workspace(g, dim, k);
     if (st != MAXK_OK) return st;
     int mode = g->bwd_mode;
-    if (mode == MAXK_BWD_AUTO) mode = MAXK_BWD_PUSH_CSR;
+    if (mode == MAXK_BWD_AUTO) mode = auto_bwd_mode(g, dim, k);
+    if (mode == MAXK_BWD_EXPAND_REDUCE) {
+        st = ensure_expand(g, k);
+        if (st != MAXK_OK) return st;
+        return launch_bwd_expand_reduce(g->csr_items, g->d_col, g->d_val, g->csc_items, g->d_csc_entry, d_dY,
+                                        d_sp_index, index_bytes, dim, k, g->d_expand, d_dXs, g->d_partials,
+                                        (hipStream_t)stream);
+    }
     if (mode == MAXK_BWD_PULL_CSC)
         return launch_bwd_pull(g->csc_items, g->d_csc_src, g->d_csc_val, d_dY, d_sp_index, index_bytes, dim, k, d_dXs,
                                g->d_partials, (hipStream_t)stream);

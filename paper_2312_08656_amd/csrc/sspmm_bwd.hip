@@ -12,12 +12,49 @@
 //    sp_index[j,:] (contiguous), gathers from LDS and adds val * dY[i, idx] into
 //    dXs[j,:] with hardware fp32 atomics (contiguous 4k bytes per entry).
 //    Needs no transposed copy of A; dXs is cleared first by a fill kernel.
+//    Bound by the rate at which L2 retires fp32 atomics (~330 G/s measured), not bytes.
+//
+//  expand/reduce (Alg. 2's staging, no atomics): phase 1 is the push kernel with
+//    the atomic replaced by a plain store of each entry's k products into a
+//    per-graph buffer in CSR entry order (one long sequential, fully coalesced
+//    write); phase 2 walks A^T in CSC order and, for destination j, gathers the
+//    4k-byte product rows of its in-entries (full cache lines, float4 per lane)
+//    and sums them in registers.  Moves 8k bytes per entry instead of 4k, but at
+//    memory bandwidth instead of atomic rate, and the result is deterministic.
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
 
 #include "common.hpp"
 
 namespace maxk {
 namespace {
+
+// VEC consecutive sp_index entries fetched with one load
+template <typename IdxT, int VEC>
+struct IdxPack;
+template <>
+struct IdxPack<uint8_t, 4> {
+    uint32_t w;
+    __device__ __forceinline__ void load(const uint8_t* p) { w = *reinterpret_cast<const uint32_t*>(p); }
+    __device__ __forceinline__ int get(int i) const { return (w >> (8 * i)) & 0xFFu; }
+};
+template <>
+struct IdxPack<uint16_t, 4> {
+    uint2 w;
+    __device__ __forceinline__ void load(const uint16_t* p) { w = *reinterpret_cast<const uint2*>(p); }
+    __device__ __forceinline__ int get(int i) const { return ((i < 2 ? w.x : w.y) >> (16 * (i & 1))) & 0xFFFFu; }
+};
+template <>
+struct IdxPack<int32_t, 4> {
+    int4 w;
+    __device__ __forceinline__ void load(const int32_t* p) { w = *reinterpret_cast<const int4*>(p); }
+    __device__ __forceinline__ int get(int i) const { return i == 0 ? w.x : i == 1 ? w.y : i == 2 ? w.z : w.w; }
+};
+template <typename IdxT>
+struct IdxPack<IdxT, 1> {
+    int w;
+    __device__ __forceinline__ void load(const IdxT* p) { w = (int)*p; }
+    __device__ __forceinline__ int get(int) const { return w; }
+};
 
 constexpr int kPullUnroll = 4;
 
@@ -153,6 +190,171 @@ __global__ __launch_bounds__(kWave) void bwd_push_kernel(const WorkItem* __restr
     }
 }
 
+// -------------------------------------------------------- expand / reduce ----
+
+constexpr int kExpandRounds = 8;
+constexpr int kReduceUnroll = 4;
+
+// Phase 1: expand[p*k + t] = val[p] * dY[row(p), sp_index[col[p]*k + t]] for every stored entry p.
+// VEC = CBSR positions per lane (4: one packed index load + one float4 store per lane; else 1).
+template <int K, int VEC, typename IdxT>
+__global__ __launch_bounds__(kWave) void bwd_expand_kernel(const WorkItem* __restrict__ items,
+                                                           const int32_t* __restrict__ col,
+                                                           const float* __restrict__ val, const float* __restrict__ dY,
+                                                           const IdxT* __restrict__ sp_index, int dim, int k_rt,
+                                                           float* __restrict__ expand)
+{
+    extern __shared__ float lds[];
+    const int lane = threadIdx.x;
+    const WorkItem it = items[blockIdx.x];
+    if (it.begin == it.end) return;
+    const int k = K ? K : k_rt;
+    const int kq = k / VEC;  // units per stored entry
+    float* __restrict__ g_row = lds;                                                  // dY[row,:]
+    int2* __restrict__ entry_buf = reinterpret_cast<int2*>(lds + ((dim + 1) & ~1));   // 64 staged (col, val)
+    const float* __restrict__ src = dY + (int64_t)it.row * dim;
+    for (int c = lane; c < dim; c += kWave) g_row[c] = src[c];
+
+    for (int base = it.begin; base < it.end; base += kWave) {
+        const int n = min(kWave, it.end - base);
+        __syncthreads();
+        if (lane < n) entry_buf[lane] = make_int2(col[base + lane], __float_as_int(val[base + lane]));
+        __syncthreads();
+        const int units = n * kq;
+        float* __restrict__ dst = expand + (int64_t)base * k;  // this batch's products are contiguous
+        for (int u0 = 0; u0 < units; u0 += kWave * kExpandRounds) {
+            IdxPack<IdxT, VEC> ix[kExpandRounds];
+            float a[kExpandRounds];
+            bool ok[kExpandRounds];
+#pragma unroll
+            for (int r = 0; r < kExpandRounds; ++r) {
+                const int u = u0 + r * kWave + lane;
+                ok[r] = u < units;
+                const int uc = ok[r] ? u : 0;
+                const int e = uc / kq;
+                const int q = uc - e * kq;
+                const int2 ed = entry_buf[e];
+                a[r] = __int_as_float(ed.y);
+                ix[r].load(sp_index + (int64_t)ed.x * k + q * VEC);
+            }
+#pragma unroll
+            for (int r = 0; r < kExpandRounds; ++r) {
+                if (ok[r]) {
+                    const int u = u0 + r * kWave + lane;
+                    if constexpr (VEC == 4) {
+                        *reinterpret_cast<float4*>(dst + (int64_t)u * 4) =
+                            make_float4(a[r] * g_row[ix[r].get(0)], a[r] * g_row[ix[r].get(1)],
+                                        a[r] * g_row[ix[r].get(2)], a[r] * g_row[ix[r].get(3)]);
+                    } else {
+                        dst[u] = a[r] * g_row[ix[r].get(0)];
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Phase 2: dXs[j, :] = sum of the product rows of j's in-entries.  VEC = floats per lane (4 or 1);
+// LPE = lanes per entry (power of two >= k / VEC, at most 64); 64 / LPE entries per wave instruction.
+template <int VEC, int LPE>
+__global__ __launch_bounds__(kWave) void bwd_reduce_kernel(const WorkItem* __restrict__ items,
+                                                           const uint32_t* __restrict__ csc_entry,
+                                                           const float* __restrict__ expand, int k,
+                                                           float* __restrict__ dXs, float* __restrict__ partials)
+{
+    constexpr int G = kWave / LPE;
+    const int lane = threadIdx.x;
+    const int q = lane % LPE, g = lane / LPE;
+    const int kq = k / VEC;  // lanes' worth of work per entry
+    const WorkItem it = items[blockIdx.x];
+    float* __restrict__ out = (it.slot < 0) ? dXs + (int64_t)it.row * k : partials + (int64_t)it.slot * k;
+    for (int qq = q; qq < ((kq + LPE - 1) / LPE) * LPE; qq += LPE) {  // one pass unless k / VEC > 64
+        const bool active = qq < kq;
+        float acc[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+        for (int p0 = it.begin; p0 < it.end; p0 += G * kReduceUnroll) {
+            float v[kReduceUnroll][VEC];
+#pragma unroll
+            for (int u = 0; u < kReduceUnroll; ++u) {
+                const int p = p0 + u * G + g;
+                const bool ok = active && p < it.end;
+                const float* __restrict__ src = expand + (int64_t)csc_entry[ok ? p : it.begin] * k + (ok ? qq : 0) * VEC;
+                if constexpr (VEC == 4) {
+                    const float4 x = ok ? *reinterpret_cast<const float4*>(src) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
+                } else {
+                    v[u][0] = ok ? *src : 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kReduceUnroll; ++u)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[j] += v[u][j];
+        }
+#pragma unroll
+        for (int off = LPE; off < kWave; off <<= 1)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[j] += __shfl_xor(acc[j], off);
+        if (g == 0 && active) {
+            if constexpr (VEC == 4) *reinterpret_cast<float4*>(out + qq * 4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            else out[qq] = acc[0];
+        }
+    }
+}
+
+template <int VEC, typename IdxT>
+maxk_status launch_expand_t(const ItemList& L, const int32_t* col, const float* val, const float* dY,
+                            const IdxT* sp_index, int dim, int k, float* expand, hipStream_t s)
+{
+    dim3 grid((unsigned)L.n_items), block(kWave);
+    const size_t lds = sizeof(float) * (size_t)((dim + 1) & ~1) + sizeof(int2) * kWave;
+#define MAXK_EXPAND(K) \
+    hipLaunchKernelGGL((bwd_expand_kernel<K, VEC, IdxT>), grid, block, lds, s, L.d_items, col, val, dY, sp_index, dim, k, expand)
+    switch (k) {
+        case 8: MAXK_EXPAND(8); break;
+        case 16: MAXK_EXPAND(16); break;
+        case 32: MAXK_EXPAND(32); break;
+        case 64: MAXK_EXPAND(64); break;
+        case 96: MAXK_EXPAND(96); break;
+        case 128: MAXK_EXPAND(128); break;
+        case 192: MAXK_EXPAND(192); break;
+        default: MAXK_EXPAND(0); break;
+    }
+#undef MAXK_EXPAND
+    MAXK_LAUNCH_CHECK();
+    return MAXK_OK;
+}
+
+template <typename IdxT>
+maxk_status launch_expand_i(const ItemList& L, const int32_t* col, const float* val, const float* dY,
+                            const IdxT* sp_index, int dim, int k, float* expand, hipStream_t s)
+{
+    const bool vec = (k % 4 == 0) && aligned(sp_index, 4 * sizeof(IdxT)) && aligned(expand, 16);
+    return vec ? launch_expand_t<4>(L, col, val, dY, sp_index, dim, k, expand, s)
+               : launch_expand_t<1>(L, col, val, dY, sp_index, dim, k, expand, s);
+}
+
+template <int VEC>
+maxk_status launch_reduce_v(const ItemList& L, const uint32_t* csc_entry, const float* expand, int k, float* dXs,
+                            float* partials, hipStream_t s)
+{
+    dim3 grid((unsigned)L.n_items), block(kWave);
+    const int kq = k / VEC;
+#define MAXK_REDUCE(LPE) \
+    hipLaunchKernelGGL((bwd_reduce_kernel<VEC, LPE>), grid, block, 0, s, L.d_items, csc_entry, expand, k, dXs, partials)
+    if (kq <= 1) MAXK_REDUCE(1);
+    else if (kq <= 2) MAXK_REDUCE(2);
+    else if (kq <= 4) MAXK_REDUCE(4);
+    else if (kq <= 8) MAXK_REDUCE(8);
+    else if (kq <= 16) MAXK_REDUCE(16);
+    else if (kq <= 32) MAXK_REDUCE(32);
+    else MAXK_REDUCE(64);
+#undef MAXK_REDUCE
+    MAXK_LAUNCH_CHECK();
+    return MAXK_OK;
+}
+
 template <typename IdxT>
 maxk_status launch_pull_t(const ItemList& L, const int32_t* csc_src, const float* csc_val, const float* dY,
                           const IdxT* sp_index, int dim, int k, float* dXs, float* partials, hipStream_t s)
@@ -230,6 +432,26 @@ maxk_status launch_bwd_push(const ItemList& L, const int32_t* col, const float* 
     if (index_bytes == 1) return launch_push_t(L, col, val, dY, (const uint8_t*)sp_index, dim, k, dXs, s);
     if (index_bytes == 2) return launch_push_t(L, col, val, dY, (const uint16_t*)sp_index, dim, k, dXs, s);
     return launch_push_t(L, col, val, dY, (const int32_t*)sp_index, dim, k, dXs, s);
+}
+
+maxk_status launch_bwd_expand_reduce(const ItemList& csr_items, const int32_t* col, const float* val,
+                                     const ItemList& csc_items, const uint32_t* csc_entry, const float* dY,
+                                     const void* sp_index, int index_bytes, int dim, int k, float* expand,
+                                     float* dXs, float* partials, hipStream_t s)
+{
+    if (csc_items.n_items == 0) return MAXK_OK;
+    if (csr_items.n_items > 0x7FFFFFFF || csc_items.n_items > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
+    maxk_status st = MAXK_OK;
+    if (csr_items.n_items) {
+        if (index_bytes == 1) st = launch_expand_i(csr_items, col, val, dY, (const uint8_t*)sp_index, dim, k, expand, s);
+        else if (index_bytes == 2) st = launch_expand_i(csr_items, col, val, dY, (const uint16_t*)sp_index, dim, k, expand, s);
+        else st = launch_expand_i(csr_items, col, val, dY, (const int32_t*)sp_index, dim, k, expand, s);
+        if (st != MAXK_OK) return st;
+    }
+    if (k % 4 == 0 && aligned(dXs, 16) && aligned(expand, 16)) st = launch_reduce_v<4>(csc_items, csc_entry, expand, k, dXs, partials, s);
+    else st = launch_reduce_v<1>(csc_items, csc_entry, expand, k, dXs, partials, s);
+    if (st != MAXK_OK) return st;
+    return launch_combine(csc_items, partials, k, dXs, s);
 }
 
 }  // namespace maxk

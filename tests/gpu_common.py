@@ -138,9 +138,12 @@ def full_pass(dg, H, dY, k, index_bytes, sampled, seed=0, n_random=1500, spmm=Tr
     say(f"    forward ok, worst err/bound {rf:.3f} ({time.time() - t0:.1f}s)")
     dX_pull, rb1 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_PULL_CSC, rows)
     dX_push, rb2 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_PUSH_CSR, rows)
-    say(f"    backward ok, worst err/bound pull {rb1:.3f} push {rb2:.3f} ({time.time() - t0:.1f}s)")
-    check_adjoint(Y, dY_dev, sp_data, dX_pull)
-    check_adjoint(Y, dY_dev, sp_data, dX_push)
+    dX_er, rb3 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_EXPAND_REDUCE, rows)
+    dX_auto, rb4 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_AUTO, rows)
+    say(f"    backward ok, worst err/bound pull {rb1:.3f} push {rb2:.3f} expand/reduce {rb3:.3f} auto {rb4:.3f} "
+        f"({time.time() - t0:.1f}s)")
+    for dX in (dX_pull, dX_push, dX_er, dX_auto):
+        check_adjoint(Y, dY_dev, sp_data, dX)
     if spmm:
         rs = check_spmm(dg, H, H_dev, rows)
         say(f"    dense SpMM ok, worst err/bound {rs:.3f} ({time.time() - t0:.1f}s)")

@@ -42,7 +42,7 @@ def test_golden_example_on_gpu():
         Y = torch.empty((N, dim), device="cuda")
         maxk.maxk_spgemm_fwd(gr, sp_data, sp_index, dim, Y)
         assert np.array_equal(Y.cpu().numpy(), np.array(g["Y"], dtype=np.float32))  # small integers: exact
-        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR):
+        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_AUTO):
             gr.set_bwd_mode(mode)
             dXs = torch.empty((N, k), device="cuda")
             maxk.maxk_sspmm_bwd(gr, to_dev(dY), sp_index, dXs)
@@ -142,6 +142,13 @@ def test_misaligned_views_take_the_scalar_paths():
     check_forward(dg, ref, sp_data, sp_index, dim)
     check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_PUSH_CSR)
     check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_PULL_CSC)
+    check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_EXPAND_REDUCE)
+    dxbuf = torch.empty(g.N * k + 1, device="cuda")  # misaligned dXs: the reduce phase takes its scalar path
+    dg.handle.set_bwd_mode(maxk.BWD_EXPAND_REDUCE)
+    maxk.maxk_sspmm_bwd(dg.handle, to_dev(dY), sp_index, dxbuf[1:].view(g.N, k))
+    dref, dabs = oracle.sspmm_bwd(g.rowptr, g.col, g.val, dY, ref[1])
+    assert (np.abs(dxbuf[1:].view(g.N, k).cpu().numpy() - dref) <= 1e-5 * dabs + 1e-6).all()
+    dg.handle.set_bwd_mode(maxk.BWD_AUTO)
     check_spmm(dg, H, Hd)
     dg.close()
 
@@ -156,7 +163,7 @@ def test_outputs_are_overwritten_and_calls_repeat():
     maxk.maxk_spgemm_fwd(dg.handle, sp_data, sp_index, 64, Y1)
     ref, refabs = oracle.spgemm_fwd(g.rowptr, g.col, g.val, *oracle.topk_cbsr(H, 8), 64)
     assert np.abs(Y1.cpu().numpy() - ref).max() < 1e-4
-    for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR):
+    for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE):
         dg.handle.set_bwd_mode(mode)
         a = torch.full((g.N, 8), 55.0, device="cuda")
         b = torch.full((g.N, 8), -7.0, device="cuda")
