@@ -69,6 +69,8 @@ def main() -> int:
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-k table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--sweep-reps", type=int, default=20)
+    ap.add_argument("--bwd-mode", default="auto", choices=["auto", "pull", "push", "expand", "slab"],
+                    help="backward kernel used in the timed steps (default: the library's choice)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference point for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -103,6 +105,9 @@ def main() -> int:
     torch.cuda.synchronize()
     t_pre = time.time() - t_pre
     kmax = max(max(cfg.ks), k0)
+    bwd_modes = {"auto": maxk.BWD_AUTO, "pull": maxk.BWD_PULL_CSC, "push": maxk.BWD_PUSH_CSR,
+                 "expand": maxk.BWD_EXPAND_REDUCE, "slab": maxk.BWD_SLAB_PULL}
+    gr.set_bwd_mode(bwd_modes[args.bwd_mode])
     gr.reserve(dim, kmax)
     Y = torch.empty((N, dim), device="cuda")
     idt = maxk.index_dtype(ib)
@@ -189,7 +194,7 @@ def main() -> int:
                    "fwd_edges_k_per_s": nnz * k / (tf * 1e-3), "fwd_hbm_frac": round(b["fwd"] / (tf * 1e-3) / 8e12, 4),
                    "fwd_speedup_vs_spmm": round(spmm_ms / tf, 2)}
             for mode, tag in ((maxk.BWD_PUSH_CSR, "bwd_push"), (maxk.BWD_PULL_CSC, "bwd_pull"),
-                              (maxk.BWD_EXPAND_REDUCE, "bwd_expand_reduce")):
+                              (maxk.BWD_EXPAND_REDUCE, "bwd_expand_reduce"), (maxk.BWD_SLAB_PULL, "bwd_slab_pull")):
                 gr.set_bwd_mode(mode)
                 reps = max(3, args.sweep_reps // 4)
                 tb, tb_med = timeit(lambda: maxk.maxk_sspmm_bwd(gr, dYd, si, dx), reps, warm=1)
@@ -241,6 +246,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: R-MAT graph N={N} nnz={nnz} (stands for: {cfg.stands_for}), "
                                f"dim={dim}, k={k0}, uint{8 * ib} sp_index, GCN weights, H,dY~N(0,1)",
                    "N": N, "nnz": nnz, "dim": dim, "k": k0, "max_degree": g.meta.get("max_degree"),
+                   "bwd_mode": args.bwd_mode,
                    "graph_handle": gr.info()},
         "step_breakdown_ms": {"topk_cbsr": round(t_topk, 4), "spgemm_fwd": round(t_fwd, 4),
                               "sspmm_bwd": round(t_bwd, 4)},

@@ -58,8 +58,10 @@ enum {
     MAXK_BWD_AUTO = 0,    /* library's choice (the faster one on MI355X) */
     MAXK_BWD_PULL_CSC = 1,/* owner-computes over A^T stored as CSC: deterministic, no atomics */
     MAXK_BWD_PUSH_CSR = 2,/* Alg. 2's dataflow: stage dY[i,:] on chip, push along row i of A with fp32 atomics */
-    MAXK_BWD_EXPAND_REDUCE = 3 /* Alg. 2's staging without atomics: write each entry's k products to a per-graph
+    MAXK_BWD_EXPAND_REDUCE = 3,/* Alg. 2's staging without atomics: write each entry's k products to a per-graph
                                   buffer (nnz*k floats, sequential), then sum them per destination node */
+    MAXK_BWD_SLAB_PULL = 4    /* owner-computes pull, tiled so the dY rows being gathered stay in L2: source rows are
+                                  swept slab by slab, one launch per slab; deterministic, no atomics */
 };
 
 typedef struct maxk_graph maxk_graph;

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     BWD_EXPAND_REDUCE,
     BWD_PULL_CSC,
     BWD_PUSH_CSR,
+    BWD_SLAB_PULL,
     MaxKError,
     MaxKGraph,
     index_dtype,

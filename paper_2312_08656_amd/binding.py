@@ -10,7 +10,7 @@ import torch
 _HERE = Path(__file__).resolve().parent
 _LIB: Optional[ctypes.CDLL] = None
 
-BWD_AUTO, BWD_PULL_CSC, BWD_PUSH_CSR, BWD_EXPAND_REDUCE = 0, 1, 2, 3
+BWD_AUTO, BWD_PULL_CSC, BWD_PUSH_CSR, BWD_EXPAND_REDUCE, BWD_SLAB_PULL = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode", "maxk_graph_info",

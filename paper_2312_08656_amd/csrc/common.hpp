@@ -36,6 +36,26 @@ struct ItemList {
     int64_t n_slots = 0;
 };
 
+// A^T regrouped for the L2-tiled pull kernel: source rows are cut into slabs of `slab_rows`
+// rows (a slab of dY fits one XCD's L2); in-entries are ordered by (slab of source, destination,
+// source) and every non-empty (slab, destination) pair is one "visit".
+struct SlabSet {
+    int32_t slab_rows = 0;
+    int32_t n_slabs = 0;
+    int64_t n_visits = 0;
+    int32_t* d_src = nullptr;          // [nnz] source row of each regrouped in-entry
+    float* d_val = nullptr;            // [nnz]
+    int32_t* d_visit_node = nullptr;   // [n_visits] destination node
+    int32_t* d_visit_begin = nullptr;  // [n_visits + 1] first regrouped entry of the visit
+    int64_t* h_slab_visit = nullptr;   // host [n_slabs + 1] first visit of each slab
+    // visits with more than kSlabLongVisit entries (hub destinations) are worked on by a whole wavefront
+    int64_t n_long = 0;
+    int32_t* d_long_visit = nullptr;   // [n_long] visit numbers, grouped by slab
+    int64_t* h_slab_long = nullptr;    // host [n_slabs + 1] first long visit of each slab
+};
+
+constexpr int kSlabLongVisit = 32;
+
 extern thread_local int32_t g_last_hip_error;
 
 inline maxk_status hip_fail(hipError_t e)
@@ -83,6 +103,12 @@ maxk_status launch_bwd_expand_reduce(const ItemList& csr_items, const int32_t* c
                                      const ItemList& csc_items, const uint32_t* csc_entry, const float* dY,
                                      const void* sp_index, int index_bytes, int dim, int k, float* expand,
                                      float* dXs, float* partials, hipStream_t s);
+
+maxk_status launch_bwd_slab_pull(const SlabSet& S, const float* dY, const void* sp_index, int index_bytes, int64_t N,
+                                 int dim, int k, float* dXs, hipStream_t s);
+
+// shared by the push and slab kernels: p[0..n) = 0
+maxk_status launch_fill_zero(float* p, int64_t n, hipStream_t s);
 
 // out[row,:] = sum of the row's partial slots, for every split row (width = row length in floats)
 maxk_status launch_combine(const ItemList& items, const float* partials, int width, float* out, hipStream_t s);

@@ -36,6 +36,7 @@ struct maxk_graph {
     int64_t partial_floats = 0;
     float* d_expand = nullptr;  // per-entry contributions of the expand/reduce backward kernel (nnz * k floats)
     int64_t expand_floats = 0;
+    maxk::SlabSet slabs;        // built on demand for one slab height at a time
     int64_t max_degree = 0;
     int32_t bwd_mode = MAXK_BWD_AUTO;
     int32_t chunk = 0;
@@ -234,6 +235,207 @@ maxk_status ensure_workspace(maxk_graph* g, int dim, int k)
     return MAXK_OK;
 }
 
+void free_slabs(SlabSet& S)
+{
+    (void)hipFree(S.d_src);
+    (void)hipFree(S.d_val);
+    (void)hipFree(S.d_visit_node);
+    (void)hipFree(S.d_visit_begin);
+    (void)hipFree(S.d_long_visit);
+    std::free(S.h_slab_visit);
+    std::free(S.h_slab_long);
+    S = SlabSet();
+}
+
+// key[q] = slab(source of CSC position q) * N + destination of q;  iota[q] = q
+__global__ __launch_bounds__(256) void slab_keys_kernel(const int32_t* __restrict__ csc_ptr,
+                                                        const int32_t* __restrict__ csc_src, int64_t N, int64_t nnz,
+                                                        int32_t slab_rows, uint64_t* __restrict__ key,
+                                                        uint32_t* __restrict__ iota)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nnz; q += stride) {
+        int64_t lo = 0, hi = N;  // largest j with csc_ptr[j] <= q
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if ((int64_t)csc_ptr[mid] <= q) lo = mid; else hi = mid;
+        }
+        key[q] = (uint64_t)(csc_src[q] / slab_rows) * (uint64_t)N + (uint64_t)lo;
+        iota[q] = (uint32_t)q;
+    }
+}
+
+__global__ __launch_bounds__(256) void slab_gather_kernel(const uint32_t* __restrict__ perm,
+                                                          const uint64_t* __restrict__ key_sorted,
+                                                          const int32_t* __restrict__ csc_src,
+                                                          const float* __restrict__ csc_val, int64_t nnz,
+                                                          int32_t* __restrict__ out_src, float* __restrict__ out_val,
+                                                          uint32_t* __restrict__ head)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < nnz; r += stride) {
+        const uint32_t q = perm[r];
+        out_src[r] = csc_src[q];
+        out_val[r] = csc_val[q];
+        head[r] = (r == 0 || key_sorted[r] != key_sorted[r - 1]) ? 1u : 0u;
+    }
+}
+
+// at every head position r (visit number v = rank[r] - 1): record the visit
+__global__ __launch_bounds__(256) void slab_visits_kernel(const uint32_t* __restrict__ head,
+                                                          const uint32_t* __restrict__ rank,
+                                                          const uint64_t* __restrict__ key_sorted, int64_t N,
+                                                          int64_t nnz, int32_t* __restrict__ visit_node,
+                                                          int32_t* __restrict__ visit_begin,
+                                                          int32_t* __restrict__ visit_slab)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < nnz; r += stride) {
+        if (!head[r]) continue;
+        const uint32_t v = rank[r] - 1u;
+        const uint64_t key = key_sorted[r];
+        visit_node[v] = (int32_t)(key % (uint64_t)N);
+        visit_slab[v] = (int32_t)(key / (uint64_t)N);
+        visit_begin[v] = (int32_t)r;
+    }
+}
+
+// slab_first[s] = first visit whose slab is >= s (slab_first pre-filled with n_visits)
+__global__ __launch_bounds__(256) void slab_first_kernel(const int32_t* __restrict__ visit_slab, int64_t n_visits,
+                                                         int64_t* __restrict__ slab_first)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n_visits; v += stride) {
+        const int32_t sl = visit_slab[v];
+        const int32_t prev = v ? visit_slab[v - 1] : -1;
+        for (int32_t s = prev + 1; s <= sl; ++s) slab_first[s] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_i64_kernel(int64_t* __restrict__ p, int64_t n, int64_t value)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+// Regroups A^T by slabs of `slab_rows` source rows (see SlabSet).  Synchronises the device.
+maxk_status build_slabs(maxk_graph* g, int32_t slab_rows)
+{
+    SlabSet& S = g->slabs;
+    if (S.slab_rows == slab_rows) return MAXK_OK;
+    MAXK_HIP_TRY(hipDeviceSynchronize());
+    free_slabs(S);
+    const int64_t N = g->N, nnz = g->nnz;
+    const int32_t n_slabs = (int32_t)((N + slab_rows - 1) / slab_rows);
+    S.h_slab_visit = (int64_t*)std::calloc((size_t)n_slabs + 1, sizeof(int64_t));
+    if (!S.h_slab_visit) return MAXK_OUT_OF_MEMORY;
+    S.n_slabs = n_slabs;
+    if (nnz == 0) {
+        S.slab_rows = slab_rows;
+        return MAXK_OK;
+    }
+    hipStream_t s = nullptr;
+    uint64_t *d_key = nullptr, *d_key_sorted = nullptr;
+    uint32_t *d_iota = nullptr, *d_perm = nullptr, *d_head = nullptr, *d_rank = nullptr;
+    int32_t* d_visit_slab = nullptr;
+    int64_t* d_slab_first = nullptr;
+    void* d_tmp = nullptr;
+    auto cleanup = [&]() {
+        (void)hipFree(d_key); (void)hipFree(d_key_sorted); (void)hipFree(d_iota); (void)hipFree(d_perm);
+        (void)hipFree(d_head); (void)hipFree(d_rank); (void)hipFree(d_visit_slab); (void)hipFree(d_slab_first);
+        (void)hipFree(d_tmp);
+    };
+#define MAXK_TRY_CLEAN(expr)                                                           \
+    do {                                                                               \
+        hipError_t _e = (expr);                                                        \
+        if (_e != hipSuccess) { cleanup(); free_slabs(S); return hip_fail(_e); }       \
+    } while (0)
+    MAXK_TRY_CLEAN(hipMalloc((void**)&S.d_src, sizeof(int32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&S.d_val, sizeof(float) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_key, sizeof(uint64_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_key_sorted, sizeof(uint64_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_iota, sizeof(uint32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_perm, sizeof(uint32_t) * (size_t)nnz));
+    const unsigned blocks = (unsigned)std::min<int64_t>((nnz + 255) / 256, 65536);
+    hipLaunchKernelGGL(slab_keys_kernel, dim3(blocks), dim3(256), 0, s, g->d_csc_ptr, g->d_csc_src, N, nnz, slab_rows,
+                       d_key, d_iota);
+    MAXK_TRY_CLEAN(hipGetLastError());
+    int end_bit = 1;
+    while (end_bit < 64 && ((uint64_t)1 << end_bit) < (uint64_t)n_slabs * (uint64_t)N) ++end_bit;
+    size_t tmp_bytes = 0;
+    MAXK_TRY_CLEAN(rocprim::radix_sort_pairs(nullptr, tmp_bytes, d_key, d_key_sorted, d_iota, d_perm, (size_t)nnz, 0,
+                                             (unsigned)end_bit, s));
+    MAXK_TRY_CLEAN(hipMalloc(&d_tmp, tmp_bytes ? tmp_bytes : 16));
+    MAXK_TRY_CLEAN(rocprim::radix_sort_pairs(d_tmp, tmp_bytes, d_key, d_key_sorted, d_iota, d_perm, (size_t)nnz, 0,
+                                             (unsigned)end_bit, s));
+    MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+    (void)hipFree(d_tmp); d_tmp = nullptr;
+    (void)hipFree(d_key); d_key = nullptr;
+    (void)hipFree(d_iota); d_iota = nullptr;
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_head, sizeof(uint32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_rank, sizeof(uint32_t) * (size_t)nnz));
+    hipLaunchKernelGGL(slab_gather_kernel, dim3(blocks), dim3(256), 0, s, d_perm, d_key_sorted, g->d_csc_src,
+                       g->d_csc_val, nnz, S.d_src, S.d_val, d_head);
+    MAXK_TRY_CLEAN(hipGetLastError());
+    tmp_bytes = 0;
+    MAXK_TRY_CLEAN(rocprim::inclusive_scan(nullptr, tmp_bytes, d_head, d_rank, (size_t)nnz, rocprim::plus<uint32_t>(), s));
+    MAXK_TRY_CLEAN(hipMalloc(&d_tmp, tmp_bytes ? tmp_bytes : 16));
+    MAXK_TRY_CLEAN(rocprim::inclusive_scan(d_tmp, tmp_bytes, d_head, d_rank, (size_t)nnz, rocprim::plus<uint32_t>(), s));
+    uint32_t n_visits32 = 0;
+    MAXK_TRY_CLEAN(hipMemcpyAsync(&n_visits32, d_rank + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+    const int64_t n_visits = n_visits32;
+    MAXK_TRY_CLEAN(hipMalloc((void**)&S.d_visit_node, sizeof(int32_t) * (size_t)n_visits));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&S.d_visit_begin, sizeof(int32_t) * (size_t)(n_visits + 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_visit_slab, sizeof(int32_t) * (size_t)n_visits));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_slab_first, sizeof(int64_t) * (size_t)(n_slabs + 1)));
+    hipLaunchKernelGGL(slab_visits_kernel, dim3(blocks), dim3(256), 0, s, d_head, d_rank, d_key_sorted, N, nnz,
+                       S.d_visit_node, S.d_visit_begin, d_visit_slab);
+    const int32_t nnz32 = (int32_t)nnz;
+    MAXK_TRY_CLEAN(hipMemcpyAsync(S.d_visit_begin + n_visits, &nnz32, sizeof(int32_t), hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(fill_i64_kernel, dim3((unsigned)((n_slabs + 1 + 255) / 256)), dim3(256), 0, s, d_slab_first,
+                       (int64_t)n_slabs + 1, n_visits);
+    hipLaunchKernelGGL(slab_first_kernel, dim3((unsigned)std::min<int64_t>((n_visits + 255) / 256, 65536)), dim3(256), 0,
+                       s, d_visit_slab, n_visits, d_slab_first);
+    MAXK_TRY_CLEAN(hipGetLastError());
+    MAXK_TRY_CLEAN(hipMemcpyAsync(S.h_slab_visit, d_slab_first, sizeof(int64_t) * (size_t)(n_slabs + 1),
+                                  hipMemcpyDeviceToHost, s));
+    MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+    // long visits (hub destinations inside one slab): listed per slab on the host
+    {
+        std::vector<int32_t> h_begin((size_t)n_visits + 1), h_long;
+        MAXK_TRY_CLEAN(hipMemcpy(h_begin.data(), S.d_visit_begin, sizeof(int32_t) * (size_t)(n_visits + 1),
+                                 hipMemcpyDeviceToHost));
+        S.h_slab_long = (int64_t*)std::calloc((size_t)n_slabs + 1, sizeof(int64_t));
+        if (!S.h_slab_long) { cleanup(); free_slabs(S); return MAXK_OUT_OF_MEMORY; }
+        for (int32_t sl = 0; sl < n_slabs; ++sl) {
+            S.h_slab_long[sl] = (int64_t)h_long.size();
+            for (int64_t v = S.h_slab_visit[sl]; v < S.h_slab_visit[sl + 1]; ++v)
+                if (h_begin[(size_t)v + 1] - h_begin[(size_t)v] > kSlabLongVisit) h_long.push_back((int32_t)v);
+        }
+        S.h_slab_long[n_slabs] = (int64_t)h_long.size();
+        S.n_long = (int64_t)h_long.size();
+        if (S.n_long) {
+            MAXK_TRY_CLEAN(hipMalloc((void**)&S.d_long_visit, sizeof(int32_t) * h_long.size()));
+            MAXK_TRY_CLEAN(hipMemcpy(S.d_long_visit, h_long.data(), sizeof(int32_t) * h_long.size(), hipMemcpyHostToDevice));
+        }
+
+    }
+#undef MAXK_TRY_CLEAN
+    cleanup();
+    S.n_visits = n_visits;
+    S.slab_rows = slab_rows;
+    return MAXK_OK;
+}
+
+// Slab height for hidden width `dim`: a slab of dY should sit comfortably inside one XCD's 4 MB L2.
+int32_t slab_rows_for(int dim)
+{
+    const int kb = env_int("MAXK_SLAB_KB", 3584, 64, 1 << 20);
+    const int64_t rows = (int64_t)kb * 1024 / ((int64_t)dim * 4);
+    return (int32_t)std::max<int64_t>(rows, 64);
+}
+
 maxk_status ensure_expand(maxk_graph* g, int k)
 {
     const int64_t need = g->nnz * (int64_t)k;
@@ -243,19 +445,25 @@ maxk_status ensure_expand(maxk_graph* g, int k)
     if (g->d_expand) {
         MAXK_HIP_TRY(hipDeviceSynchronize());
         (void)hipFree(g->d_expand);
+    free_slabs(g->slabs);
     }
     g->d_expand = fresh;
     g->expand_floats = need;
     return MAXK_OK;
 }
 
-// Backward kernel choice when the caller leaves it to the library.  Expand/reduce moves
-// 8k bytes per stored entry through HBM, pull touches about min(k, dim/32) cache lines of a
-// dY row per entry whatever k is, so pull wins once k is a large share of dim.
+// Backward kernel choice when the caller leaves it to the library (rates measured on MI355X).
+// Slab pull gathers dY from L2 but re-reads and re-writes a destination's dXs row once per
+// (slab, destination) visit, so it needs several in-entries per visit: dense neighbourhoods.
+// Otherwise: expand/reduce moves 8k bytes per stored entry through HBM, plain pull touches about
+// min(k, dim/32) cache lines of a dY row per entry whatever k is, so pull wins once k is large.
 int auto_bwd_mode(const maxk_graph* g, int dim, int k)
 {
+    const double n_slabs = std::ceil((double)g->N / slab_rows_for(dim));
+    const double entries_per_visit = (double)g->nnz / std::max(1.0, (double)g->N * n_slabs);
+    if (entries_per_visit >= 2.0 && n_slabs * (double)g->N < 1.8e19) return MAXK_BWD_SLAB_PULL;
     const double lines = (dim / 32.0) * (1.0 - std::pow(1.0 - 32.0 / dim, (double)k));  // expected lines touched
-    const double pull_cost = (dim <= 32 ? 1.0 : lines) * 128.0 / 8.5;                  // bytes / (TB/s), measured rates
+    const double pull_cost = (dim <= 32 ? 1.0 : lines) * 128.0 / 8.5;                  // bytes / (TB/s)
     const double expand_cost = 8.0 * k / 4.3;
     const bool fits = (double)g->nnz * k * 4.0 <= 96e9;
     return (fits && expand_cost < pull_cost) ? MAXK_BWD_EXPAND_REDUCE : MAXK_BWD_PULL_CSC;
@@ -342,6 +550,7 @@ MAXK_API maxk_status maxk_graph_destroy(maxk_graph* g)
     (void)hipFree(g->d_csc_val);
     (void)hipFree(g->d_csc_entry);
     (void)hipFree(g->d_expand);
+    free_slabs(g->slabs);
     (void)hipFree(g->d_partials);
     delete g;
     return MAXK_OK;
@@ -354,12 +563,13 @@ MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k)
     maxk_status st = ensure_workspace(g, dim, k);
     if (st != MAXK_OK) return st;
     const int mode = g->bwd_mode == MAXK_BWD_AUTO ? auto_bwd_mode(g, dim, k) : g->bwd_mode;
+    if (mode == MAXK_BWD_SLAB_PULL) return build_slabs(g, slab_rows_for(dim));
     return mode == MAXK_BWD_EXPAND_REDUCE ? ensure_expand(g, k) : MAXK_OK;
 }
 
 MAXK_API maxk_status maxk_graph_set_bwd_mode(maxk_graph* g, int32_t mode)
 {
-    if (!g || mode < MAXK_BWD_AUTO || mode > MAXK_BWD_EXPAND_REDUCE) return MAXK_INVALID_ARGUMENT;
+    if (!g || mode < MAXK_BWD_AUTO || mode > MAXK_BWD_SLAB_PULL) return MAXK_INVALID_ARGUMENT;
     g->bwd_mode = mode;
     return MAXK_OK;
 }
@@ -418,6 +628,11 @@ MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void
     if (st != MAXK_OK) return st;
     int mode = g->bwd_mode;
     if (mode == MAXK_BWD_AUTO) mode = auto_bwd_mode(g, dim, k);
+    if (mode == MAXK_BWD_SLAB_PULL) {
+        st = build_slabs(g, slab_rows_for(dim));
+        if (st != MAXK_OK) return st;
+        return launch_bwd_slab_pull(g->slabs, d_dY, d_sp_index, index_bytes, g->N, dim, k, d_dXs, (hipStream_t)stream);
+    }
     if (mode == MAXK_BWD_EXPAND_REDUCE) {
         st = ensure_expand(g, k);
         if (st != MAXK_OK) return st;

@@ -21,7 +21,21 @@
 //    4k-byte product rows of its in-entries (full cache lines, float4 per lane)
 //    and sums them in registers.  Moves 8k bytes per entry instead of 4k, but at
 //    memory bandwidth instead of atomic rate, and the result is deterministic.
+//
+//  slab pull (owner computes, tiled for L2): the pull kernel is bound by fetching
+//    ~dim/32 cache lines of a dY row per entry from beyond L2 (~7 G rows/s at
+//    dim 256); the same sampled gather runs at ~30 G rows/s when the rows sit in
+//    the XCD's 4 MB L2.  So the source rows are swept in slabs of a few MB of dY,
+//    ONE LAUNCH PER SLAB (every XCD gathers from the same slab, so each L2 holds
+//    one copy; the launch boundary is what keeps all wavefronts on one slab --
+//    letting them run ahead into the next slab was measured to lose the locality,
+//    and it would also race on dXs): a launch walks the non-empty
+//    (slab, destination) visits and adds the visit's in-entries to the
+//    destination's dXs row (read-modify-write, the row is revisited once per
+//    slab).  Pays off when a visit has several entries, i.e. dense neighbourhoods.
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
+
+#include <algorithm>
 
 #include "common.hpp"
 
@@ -355,6 +369,184 @@ maxk_status launch_reduce_v(const ItemList& L, const uint32_t* csc_entry, const 
     return MAXK_OK;
 }
 
+// ------------------------------------------------------------- slab pull ----
+
+// VEC CBSR positions per lane, STRIDED: lane q of a visit holds positions q, q + k/VEC, q + 2k/VEC, ...
+// so that one gather instruction covers k/VEC CONSECUTIVE (ascending-column) positions of each visit
+// and every cache line of a dY row is requested by one instruction only;
+// LPD lanes per destination (power of two >= min(k / VEC, 64)); 64 / LPD visits per wave step.
+// The visit header of the next step is fetched while the current one is processed.
+// Visits longer than kSlabLongVisit entries are skipped by the lane groups and worked on by whole
+// wavefronts instead (the first n_long_blocks workgroups): the 64 / LPD groups take every G-th entry
+// and their sums are added across the wave, so a hub destination does not become the launch's tail.
+// Within one launch every destination occurs in at most one visit, so the read-modify-write of its
+// dXs row needs no atomics; launches of consecutive slabs are ordered by the stream.
+template <int VEC, int LPD, typename IdxT>
+__global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restrict__ visit_node,
+                                                         const int32_t* __restrict__ visit_begin, int64_t v_begin,
+                                                         int64_t v_end, const int32_t* __restrict__ long_visit,
+                                                         int64_t l_begin, int64_t l_end, int n_long_blocks,
+                                                         const int32_t* __restrict__ slab_src,
+                                                         const float* __restrict__ slab_val,
+                                                         const float* __restrict__ dY,
+                                                         const IdxT* __restrict__ sp_index, int dim, int k,
+                                                         float* __restrict__ dXs)
+{
+    constexpr int G = kWave / LPD;
+    const int lane = threadIdx.x;
+    const int q0 = lane % LPD, g = lane / LPD;
+    const int kq = k / VEC;
+    if ((int)blockIdx.x < n_long_blocks) {
+        for (int64_t l = l_begin + blockIdx.x; l < l_end; l += n_long_blocks) {
+            const int64_t v = long_visit[l];
+            const int64_t j = visit_node[v];
+            const int b = visit_begin[v], e = visit_begin[v + 1];
+            for (int qb = 0; qb < kq; qb += LPD) {  // one pass unless k / VEC > 64
+                const int q = qb + q0;
+                const bool active = q < kq;
+                const int64_t o = j * k + (active ? q : 0);  // lane's positions: o + c * kq
+                int64_t my[VEC];
+                float acc[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    my[c] = (int64_t)sp_index[o + c * kq];
+                    acc[c] = 0.f;
+                }
+                for (int p0 = b; p0 < e; p0 += G * 4) {
+                    float gv[4][VEC], a[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int p = p0 + u * G + g;
+                        const bool ok = p < e;
+                        const int pc = ok ? p : b;
+                        const float* __restrict__ row = dY + (int64_t)slab_src[pc] * dim;
+                        a[u] = ok ? slab_val[pc] : 0.f;
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) {
+                            const float x = row[my[c]];
+                            gv[u][c] = ok ? x : 0.f;
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc[c] += a[u] * gv[u][c];
+                }
+#pragma unroll
+                for (int off = LPD; off < kWave; off <<= 1)
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) acc[c] += __shfl_xor(acc[c], off);
+                if (g == 0 && active) {
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) dXs[o + c * kq] += acc[c];
+                }
+            }
+        }
+        return;
+    }
+    const int64_t first = (int64_t)(blockIdx.x - n_long_blocks) * G;
+    const int64_t stride = (int64_t)(gridDim.x - n_long_blocks) * G;
+    int64_t v = v_begin + first + g;
+    bool have = v < v_end;
+    int64_t j = have ? visit_node[v] : 0;
+    int b = have ? visit_begin[v] : 0, e = have ? visit_begin[v + 1] : 0;
+    // all lanes of a wave run the same number of steps (uniform loop), idle groups just skip the work
+    for (int64_t v0 = v_begin + first; v0 < v_end; v0 += stride) {
+        const int64_t vn = v + stride;
+        const bool have_n = vn < v_end;
+        const int64_t jn = have_n ? visit_node[vn] : 0;
+        const int bn = have_n ? visit_begin[vn] : 0, en = have_n ? visit_begin[vn + 1] : 0;
+        if (have && e - b <= kSlabLongVisit) {
+            for (int q = q0; q < kq; q += LPD) {  // one pass unless k / VEC > 64
+                const int64_t o = j * k + q;  // lane's positions: o + c * kq
+                int64_t my[VEC];
+                float acc[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    my[c] = (int64_t)sp_index[o + c * kq];
+                    acc[c] = dXs[o + c * kq];
+                }
+                int p = b;
+                for (; p + 4 <= e; p += 4) {
+                    float gv[4][VEC], a[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const float* __restrict__ row = dY + (int64_t)slab_src[p + u] * dim;
+                        a[u] = slab_val[p + u];
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) gv[u][c] = row[my[c]];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc[c] += a[u] * gv[u][c];
+                }
+                if (p < e) {  // 1..3 left: fetched together, out-of-range ones contribute zero
+                    float gv[3][VEC], a[3];
+#pragma unroll
+                    for (int u = 0; u < 3; ++u) {
+                        const bool ok = p + u < e;
+                        const int pc = ok ? p + u : b;
+                        const float* __restrict__ row = dY + (int64_t)slab_src[pc] * dim;
+                        a[u] = ok ? slab_val[pc] : 0.f;
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) {
+                            const float x = row[my[c]];
+                            gv[u][c] = ok ? x : 0.f;
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 3; ++u)
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc[c] += a[u] * gv[u][c];
+                }
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) dXs[o + c * kq] = acc[c];
+            }
+        }
+        v = vn; have = have_n; j = jn; b = bn; e = en;
+    }
+}
+
+template <int VEC, typename IdxT>
+maxk_status launch_slab_t(const SlabSet& S, const float* dY, const IdxT* sp_index, int dim, int k, float* dXs,
+                          hipStream_t s)
+{
+    const int kq = k / VEC;
+    for (int32_t sl = 0; sl < S.n_slabs; ++sl) {
+        const int64_t vb = S.h_slab_visit[sl], ve = S.h_slab_visit[sl + 1];
+        if (vb >= ve) continue;
+        const int64_t lb = S.h_slab_long[sl], le = S.h_slab_long[sl + 1];
+        const int nlb = (int)std::min<int64_t>(le - lb, 4096);
+#define MAXK_SLAB(LPD)                                                                                             \
+    do {                                                                                                           \
+        const int64_t tasks = (ve - vb + (kWave / LPD) - 1) / (kWave / LPD);                                       \
+        const unsigned grid = (unsigned)std::min<int64_t>(tasks, 256 * 32);                                        \
+        hipLaunchKernelGGL((bwd_slab_kernel<VEC, LPD, IdxT>), dim3(grid + (unsigned)nlb), dim3(kWave), 0, s,      \
+                           S.d_visit_node, S.d_visit_begin, vb, ve, S.d_long_visit, lb, le, nlb, S.d_src, S.d_val, \
+                           dY, sp_index, dim, k, dXs);                                                             \
+    } while (0)
+        if (kq <= 1) MAXK_SLAB(1);
+        else if (kq <= 2) MAXK_SLAB(2);
+        else if (kq <= 4) MAXK_SLAB(4);
+        else if (kq <= 8) MAXK_SLAB(8);
+        else if (kq <= 16) MAXK_SLAB(16);
+        else if (kq <= 32) MAXK_SLAB(32);
+        else MAXK_SLAB(64);
+#undef MAXK_SLAB
+    }
+    MAXK_LAUNCH_CHECK();
+    return MAXK_OK;
+}
+
+template <typename IdxT>
+maxk_status launch_slab_i(const SlabSet& S, const float* dY, const IdxT* sp_index, int dim, int k, float* dXs,
+                          hipStream_t s)
+{
+    return (k % 4 == 0) ? launch_slab_t<4>(S, dY, sp_index, dim, k, dXs, s)
+                        : launch_slab_t<1>(S, dY, sp_index, dim, k, dXs, s);
+}
+
 template <typename IdxT>
 maxk_status launch_pull_t(const ItemList& L, const int32_t* csc_src, const float* csc_val, const float* dY,
                           const IdxT* sp_index, int dim, int k, float* dXs, float* partials, hipStream_t s)
@@ -452,6 +644,26 @@ maxk_status launch_bwd_expand_reduce(const ItemList& csr_items, const int32_t* c
     else st = launch_reduce_v<1>(csc_items, csc_entry, expand, k, dXs, partials, s);
     if (st != MAXK_OK) return st;
     return launch_combine(csc_items, partials, k, dXs, s);
+}
+
+maxk_status launch_fill_zero(float* p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return MAXK_OK;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, n);
+    MAXK_LAUNCH_CHECK();
+    return MAXK_OK;
+}
+
+maxk_status launch_bwd_slab_pull(const SlabSet& S, const float* dY, const void* sp_index, int index_bytes, int64_t N,
+                                 int dim, int k, float* dXs, hipStream_t s)
+{
+    maxk_status st = launch_fill_zero(dXs, N * (int64_t)k, s);
+    if (st != MAXK_OK || S.n_visits == 0) return st;
+    if (index_bytes == 1) return launch_slab_i(S, dY, (const uint8_t*)sp_index, dim, k, dXs, s);
+    if (index_bytes == 2) return launch_slab_i(S, dY, (const uint16_t*)sp_index, dim, k, dXs, s);
+    return launch_slab_i(S, dY, (const int32_t*)sp_index, dim, k, dXs, s);
 }
 
 }  // namespace maxk

@@ -140,9 +140,10 @@ def full_pass(dg, H, dY, k, index_bytes, sampled, seed=0, n_random=1500, spmm=Tr
     dX_push, rb2 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_PUSH_CSR, rows)
     dX_er, rb3 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_EXPAND_REDUCE, rows)
     dX_auto, rb4 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_AUTO, rows)
+    dX_slab, rb5 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_SLAB_PULL, rows)
     say(f"    backward ok, worst err/bound pull {rb1:.3f} push {rb2:.3f} expand/reduce {rb3:.3f} auto {rb4:.3f} "
-        f"({time.time() - t0:.1f}s)")
-    for dX in (dX_pull, dX_push, dX_er, dX_auto):
+        f"slab {rb5:.3f} ({time.time() - t0:.1f}s)")
+    for dX in (dX_pull, dX_push, dX_er, dX_auto, dX_slab):
         check_adjoint(Y, dY_dev, sp_data, dX)
     if spmm:
         rs = check_spmm(dg, H, H_dev, rows)

@@ -23,6 +23,15 @@ def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     maxk.load_library()  # fails loudly if libmaxk.so is missing: there is no fallback
+    # small slabs, so that the L2-tiled backward kernel sweeps several slabs even on these small graphs
+    import os
+    old = os.environ.get("MAXK_SLAB_KB")
+    os.environ["MAXK_SLAB_KB"] = "64"
+    yield
+    if old is None:
+        os.environ.pop("MAXK_SLAB_KB", None)
+    else:
+        os.environ["MAXK_SLAB_KB"] = old
 
 
 # ------------------------------------------------------------------ small, element by element
@@ -42,7 +51,7 @@ def test_golden_example_on_gpu():
         Y = torch.empty((N, dim), device="cuda")
         maxk.maxk_spgemm_fwd(gr, sp_data, sp_index, dim, Y)
         assert np.array_equal(Y.cpu().numpy(), np.array(g["Y"], dtype=np.float32))  # small integers: exact
-        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_AUTO):
+        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_SLAB_PULL, maxk.BWD_AUTO):
             gr.set_bwd_mode(mode)
             dXs = torch.empty((N, k), device="cuda")
             maxk.maxk_sspmm_bwd(gr, to_dev(dY), sp_index, dXs)
@@ -70,6 +79,17 @@ def test_odd_shapes_and_index_widths(dim, k, ib):
                          weights="normal")
     dg = DeviceGraph(g)
     H, dY = synth.normal_matrix(g.N, dim, 3), synth.normal_matrix(g.N, dim, 4)
+    full_pass(dg, H, dY, k, ib, sampled=False)
+    dg.close()
+
+
+@pytest.mark.parametrize("dim,k,ib", [(64, 8, 1), (64, 20, 1), (256, 32, 1), (384, 96, 2), (128, 5, 4)])
+def test_small_dense_graph_with_long_slab_visits(dim, k, ib):
+    # average degree ~170 on 400 nodes: with the small test slabs many (slab, destination) visits hold more
+    # than 32 entries, which the slab kernel hands to whole wavefronts; rows also exceed one 64-entry batch
+    g = synth.make_graph(400, 34000, 0, directed=True, self_loops=True, seed=dim + k, weights="normal")
+    dg = DeviceGraph(g)
+    H, dY = synth.normal_matrix(g.N, dim, 5), synth.normal_matrix(g.N, dim, 6)
     full_pass(dg, H, dY, k, ib, sampled=False)
     dg.close()
 
@@ -163,7 +183,7 @@ def test_outputs_are_overwritten_and_calls_repeat():
     maxk.maxk_spgemm_fwd(dg.handle, sp_data, sp_index, 64, Y1)
     ref, refabs = oracle.spgemm_fwd(g.rowptr, g.col, g.val, *oracle.topk_cbsr(H, 8), 64)
     assert np.abs(Y1.cpu().numpy() - ref).max() < 1e-4
-    for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE):
+    for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_SLAB_PULL):
         dg.handle.set_bwd_mode(mode)
         a = torch.full((g.N, 8), 55.0, device="cuda")
         b = torch.full((g.N, 8), -7.0, device="cuda")
