@@ -84,9 +84,11 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 maxk_status launch_topk(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
                         hipStream_t s);
 
+// `packed`: workspace of N * fwd_packed_record_bytes(k, index_bytes) bytes to use the packed-record path, or null
 maxk_status launch_spgemm_fwd(const ItemList& items, const int32_t* col, const float* val, const float* sp_data,
-                              const void* sp_index, int index_bytes, int dim, int k, float* Y, float* partials,
-                              hipStream_t s);
+                              const void* sp_index, int index_bytes, int64_t N, char* packed, int dim, int k,
+                              float* Y, float* partials, hipStream_t s);
+int fwd_packed_record_bytes(int k, int index_bytes);
 
 maxk_status launch_spmm(const ItemList& items, const int32_t* col, const float* val, const float* H, int dim,
                         float* Y, float* partials, hipStream_t s);

@@ -37,6 +37,8 @@ struct maxk_graph {
     float* d_expand = nullptr;  // per-entry contributions of the expand/reduce backward kernel (nnz * k floats)
     int64_t expand_floats = 0;
     maxk::SlabSet slabs;        // built on demand for one slab height at a time
+    char* d_packed = nullptr;   // forward kernel's per-call repack of a small-k CBSR (one record per node)
+    int64_t packed_bytes = 0;
     int64_t max_degree = 0;
     int32_t bwd_mode = MAXK_BWD_AUTO;
     int32_t chunk = 0;
@@ -436,6 +438,27 @@ int32_t slab_rows_for(int dim)
     return (int32_t)std::max<int64_t>(rows, 64);
 }
 
+// The forward kernel repacks the CBSR when a row of it is well below a cache line.
+bool fwd_uses_packed(int k, int index_bytes)
+{
+    return k * (4 + index_bytes) <= env_int("MAXK_FWD_PACK_MAX", 96, 0, 1 << 20);
+}
+
+maxk_status ensure_packed(maxk_graph* g, int k, int index_bytes)
+{
+    const int64_t need = g->N * (int64_t)fwd_packed_record_bytes(k, index_bytes);
+    if (need <= g->packed_bytes) return MAXK_OK;
+    char* fresh = nullptr;
+    MAXK_HIP_TRY(hipMalloc((void**)&fresh, (size_t)need));
+    if (g->d_packed) {
+        MAXK_HIP_TRY(hipDeviceSynchronize());
+        (void)hipFree(g->d_packed);
+    }
+    g->d_packed = fresh;
+    g->packed_bytes = need;
+    return MAXK_OK;
+}
+
 maxk_status ensure_expand(maxk_graph* g, int k)
 {
     const int64_t need = g->nnz * (int64_t)k;
@@ -445,7 +468,6 @@ maxk_status ensure_expand(maxk_graph* g, int k)
     if (g->d_expand) {
         MAXK_HIP_TRY(hipDeviceSynchronize());
         (void)hipFree(g->d_expand);
-    free_slabs(g->slabs);
     }
     g->d_expand = fresh;
     g->expand_floats = need;
@@ -550,6 +572,7 @@ MAXK_API maxk_status maxk_graph_destroy(maxk_graph* g)
     (void)hipFree(g->d_csc_val);
     (void)hipFree(g->d_csc_entry);
     (void)hipFree(g->d_expand);
+    (void)hipFree(g->d_packed);
     free_slabs(g->slabs);
     (void)hipFree(g->d_partials);
     delete g;
@@ -562,6 +585,15 @@ MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k)
     if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
     maxk_status st = ensure_workspace(g, dim, k);
     if (st != MAXK_OK) return st;
+    for (int ib = 1; ib <= 4; ib *= 2) {
+        for (int kk = 1; kk <= k; ++kk) {  // the largest repacked record among k' <= k
+            if (!fwd_uses_packed(kk, ib)) break;
+            if (kk == k || !fwd_uses_packed(kk + 1, ib)) {
+                st = ensure_packed(g, kk, ib);
+                if (st != MAXK_OK) return st;
+            }
+        }
+    }
     const int mode = g->bwd_mode == MAXK_BWD_AUTO ? auto_bwd_mode(g, dim, k) : g->bwd_mode;
     if (mode == MAXK_BWD_SLAB_PULL) return build_slabs(g, slab_rows_for(dim));
     return mode == MAXK_BWD_EXPAND_REDUCE ? ensure_expand(g, k) : MAXK_OK;
@@ -583,7 +615,8 @@ MAXK_API maxk_status maxk_graph_info(const maxk_graph* g, int64_t* N, int64_t* n
     if (n_fwd_items) *n_fwd_items = g->csr_items.n_items;
     if (n_split_rows) *n_split_rows = g->csr_items.n_split;
     if (max_degree) *max_degree = g->max_degree;
-    if (workspace_bytes) *workspace_bytes = (g->partial_floats + g->expand_floats) * (int64_t)sizeof(float);
+    if (workspace_bytes)
+        *workspace_bytes = (g->partial_floats + g->expand_floats) * (int64_t)sizeof(float) + g->packed_bytes;
     return MAXK_OK;
 }
 
@@ -611,7 +644,13 @@ MAXK_API maxk_status maxk_spgemm_fwd(maxk_graph* g, const float* d_sp_data, cons
         return MAXK_INVALID_ARGUMENT;
     maxk_status st = ensure_workspace(g, dim, k);
     if (st != MAXK_OK) return st;
-    return launch_spgemm_fwd(g->csr_items, g->d_col, g->d_val, d_sp_data, d_sp_index, index_bytes, dim, k, d_Y,
+    char* packed = nullptr;
+    if (fwd_uses_packed(k, index_bytes)) {
+        st = ensure_packed(g, k, index_bytes);
+        if (st != MAXK_OK) return st;
+        packed = g->d_packed;
+    }
+    return launch_spgemm_fwd(g->csr_items, g->d_col, g->d_val, d_sp_data, d_sp_index, index_bytes, g->N, packed, dim, k, d_Y,
                              g->d_partials, (hipStream_t)stream);
 }
 

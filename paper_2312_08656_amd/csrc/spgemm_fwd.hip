@@ -22,6 +22,8 @@
 // every other row is written once, straight from LDS, fully coalesced.
 // Shapes whose private copies would not fit comfortably in LDS (tiny k with a
 // very wide row) fall back to the single-copy kernel with LDS atomics.
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace maxk {
@@ -141,14 +143,35 @@ __host__ __device__ constexpr int private_copies(int k)
     return (k >= kWave) ? ((k % kWave == 0) ? 1 : 2) : ((kWave % k == 0) ? kWave / k : (kWave - 1) / k + 2);
 }
 
-// K: MaxK k when known at compile time (0 = runtime); ROUNDS: 64-unit rounds in flight
-template <int K, int ROUNDS, typename IdxT>
+// For small k a CBSR row is a fraction of a cache line in EACH of the two arrays, and the kernel is
+// bound by the number of row requests (~137 G/s measured), not by bytes.  The packed path reads a
+// per-call repack instead: one record per node, k values followed by k indices, so an entry costs
+// one request.  The repack reads and writes N*k*(4+ib) bytes, against nnz*k*(4+ib) for the kernel.
+template <typename IdxT>
+__global__ __launch_bounds__(256) void pack_cbsr_kernel(const float* __restrict__ sp_data,
+                                                        const IdxT* __restrict__ sp_index, int64_t n_units, int k,
+                                                        int rec_bytes, char* __restrict__ packed)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < n_units; u += stride) {
+        const int64_t node = u / k;
+        const int t = (int)(u - node * k);
+        char* rec = packed + node * rec_bytes;
+        reinterpret_cast<float*>(rec)[t] = sp_data[u];
+        reinterpret_cast<IdxT*>(rec + 4 * k)[t] = sp_index[u];
+    }
+}
+
+// K: MaxK k when known at compile time (0 = runtime); ROUNDS: 64-unit rounds in flight;
+// PACKED: read the per-node (values, indices) records of pack_cbsr_kernel instead of the two arrays
+template <int K, int ROUNDS, bool PACKED, typename IdxT>
 __global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* __restrict__ items,
                                                                const int32_t* __restrict__ col,
                                                                const float* __restrict__ val,
                                                                const float* __restrict__ sp_data,
-                                                               const IdxT* __restrict__ sp_index, int dim, int k_rt,
-                                                               int nb_rt, float* __restrict__ Y,
+                                                               const IdxT* __restrict__ sp_index,
+                                                               const char* __restrict__ packed, int rec_bytes,
+                                                               int dim, int k_rt, int nb_rt, float* __restrict__ Y,
                                                                float* __restrict__ partials)
 {
     extern __shared__ float lds[];
@@ -179,9 +202,15 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* _
                 const int t = uc - e * k;
                 const int2 ed = entry_buf[e];
                 a[r] = __int_as_float(ed.y);
-                const int64_t off = (int64_t)ed.x * k + t;
-                d[r] = sp_data[off];
-                at[r] = (e % nb) * dim + (int)sp_index[off];
+                if constexpr (PACKED) {
+                    const char* rec = packed + (int64_t)ed.x * rec_bytes;
+                    d[r] = reinterpret_cast<const float*>(rec)[t];
+                    at[r] = (e % nb) * dim + (int)reinterpret_cast<const IdxT*>(rec + 4 * k)[t];
+                } else {
+                    const int64_t off = (int64_t)ed.x * k + t;
+                    d[r] = sp_data[off];
+                    at[r] = (e % nb) * dim + (int)sp_index[off];
+                }
             }
 #pragma unroll
             for (int r = 0; r < ROUNDS; ++r) {
@@ -249,17 +278,18 @@ maxk_status launch_ku(const ItemList& L, const int32_t* col, const float* val, c
 
 constexpr size_t kMaxPrivateLds = 40 * 1024;  // above this the private copies cost too much occupancy
 
-template <typename IdxT>
+template <bool PACKED, typename IdxT>
 maxk_status launch_rmw(const ItemList& L, const int32_t* col, const float* val, const float* sp_data,
-                       const IdxT* sp_index, int dim, int k, float* Y, float* partials, hipStream_t s)
+                       const IdxT* sp_index, const char* packed, int rec_bytes, int dim, int k, float* Y,
+                       float* partials, hipStream_t s)
 {
     if (L.n_items > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
     dim3 grid((unsigned)L.n_items), block(kWave);
     const int nb = private_copies(k);
     const size_t lds = sizeof(float) * (size_t)((nb * dim + 1) & ~1) + sizeof(int2) * kWave;
 #define MAXK_FWD_RMW(K, R)                                                                                        \
-    hipLaunchKernelGGL((spgemm_fwd_rmw_kernel<K, R, IdxT>), grid, block, lds, s, L.d_items, col, val, sp_data,    \
-                       sp_index, dim, k, nb, Y, partials)
+    hipLaunchKernelGGL((spgemm_fwd_rmw_kernel<K, R, PACKED, IdxT>), grid, block, lds, s, L.d_items, col, val,     \
+                       sp_data, sp_index, packed, rec_bytes, dim, k, nb, Y, partials)
     switch (k) {
         case 8: MAXK_FWD_RMW(8, 8); break;
         case 16: MAXK_FWD_RMW(16, 8); break;
@@ -275,6 +305,23 @@ maxk_status launch_rmw(const ItemList& L, const int32_t* col, const float* val, 
     return MAXK_OK;
 }
 
+template <typename IdxT>
+maxk_status launch_rmw_i(const ItemList& L, const int32_t* col, const float* val, const float* sp_data,
+                         const IdxT* sp_index, int64_t N, char* packed, int dim, int k, float* Y, float* partials,
+                         hipStream_t s)
+{
+    if (packed) {
+        const int rec_bytes = fwd_packed_record_bytes(k, (int)sizeof(IdxT));
+        const int64_t n_units = N * (int64_t)k;
+        const unsigned blocks = (unsigned)std::min<int64_t>((n_units + 255) / 256, 65536);
+        hipLaunchKernelGGL((pack_cbsr_kernel<IdxT>), dim3(blocks), dim3(256), 0, s, sp_data, sp_index, n_units, k,
+                           rec_bytes, packed);
+        MAXK_LAUNCH_CHECK();
+        return launch_rmw<true>(L, col, val, sp_data, sp_index, packed, rec_bytes, dim, k, Y, partials, s);
+    }
+    return launch_rmw<false>(L, col, val, sp_data, sp_index, nullptr, 0, dim, k, Y, partials, s);
+}
+
 }  // namespace
 
 maxk_status launch_combine(const ItemList& L, const float* partials, int width, float* out, hipStream_t s)
@@ -287,17 +334,19 @@ maxk_status launch_combine(const ItemList& L, const float* partials, int width, 
     return MAXK_OK;
 }
 
+int fwd_packed_record_bytes(int k, int index_bytes) { return (k * (4 + index_bytes) + 3) & ~3; }
+
 maxk_status launch_spgemm_fwd(const ItemList& L, const int32_t* col, const float* val, const float* sp_data,
-                              const void* sp_index, int index_bytes, int dim, int k, float* Y, float* partials,
-                              hipStream_t s)
+                              const void* sp_index, int index_bytes, int64_t N, char* packed, int dim, int k,
+                              float* Y, float* partials, hipStream_t s)
 {
     if (L.n_items == 0) return MAXK_OK;
     maxk_status st;
     const size_t private_lds = sizeof(float) * (size_t)private_copies(k) * (size_t)dim;
     if (private_lds <= kMaxPrivateLds) {
-        if (index_bytes == 1) st = launch_rmw(L, col, val, sp_data, (const uint8_t*)sp_index, dim, k, Y, partials, s);
-        else if (index_bytes == 2) st = launch_rmw(L, col, val, sp_data, (const uint16_t*)sp_index, dim, k, Y, partials, s);
-        else st = launch_rmw(L, col, val, sp_data, (const int32_t*)sp_index, dim, k, Y, partials, s);
+        if (index_bytes == 1) st = launch_rmw_i(L, col, val, sp_data, (const uint8_t*)sp_index, N, packed, dim, k, Y, partials, s);
+        else if (index_bytes == 2) st = launch_rmw_i(L, col, val, sp_data, (const uint16_t*)sp_index, N, packed, dim, k, Y, partials, s);
+        else st = launch_rmw_i(L, col, val, sp_data, (const int32_t*)sp_index, N, packed, dim, k, Y, partials, s);
     } else {
         if (index_bytes == 1) st = launch_ku<1>(L, col, val, sp_data, (const uint8_t*)sp_index, dim, k, Y, partials, s);
         else if (index_bytes == 2) st = launch_ku<1>(L, col, val, sp_data, (const uint16_t*)sp_index, dim, k, Y, partials, s);

@@ -371,6 +371,20 @@ maxk_status launch_reduce_v(const ItemList& L, const uint32_t* csc_entry, const 
 
 // ------------------------------------------------------------- slab pull ----
 
+// dY[row * dim + col] with the element offset held in 32 bits when OFF32 (the launcher checks
+// that the whole of dY spans less than 4 GiB): one SGPR base + 32-bit lane offsets instead of
+// 64-bit lane addresses, which is what keeps the kernel at 8 waves per SIMD.
+template <bool OFF32>
+__device__ __forceinline__ float load_sampled(const float* __restrict__ dY, int32_t row, int dim, int32_t col)
+{
+    if constexpr (OFF32) {
+        const uint32_t byte_off = ((uint32_t)row * (uint32_t)dim + (uint32_t)col) * 4u;
+        return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(dY) + byte_off);
+    } else {
+        return dY[(int64_t)row * dim + col];
+    }
+}
+
 // VEC CBSR positions per lane, STRIDED: lane q of a visit holds positions q, q + k/VEC, q + 2k/VEC, ...
 // so that one gather instruction covers k/VEC CONSECUTIVE (ascending-column) positions of each visit
 // and every cache line of a dY row is requested by one instruction only;
@@ -381,7 +395,7 @@ maxk_status launch_reduce_v(const ItemList& L, const uint32_t* csc_entry, const 
 // and their sums are added across the wave, so a hub destination does not become the launch's tail.
 // Within one launch every destination occurs in at most one visit, so the read-modify-write of its
 // dXs row needs no atomics; launches of consecutive slabs are ordered by the stream.
-template <int VEC, int LPD, typename IdxT>
+template <int VEC, int LPD, bool OFF32, typename IdxT>
 __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restrict__ visit_node,
                                                          const int32_t* __restrict__ visit_begin, int64_t v_begin,
                                                          int64_t v_end, const int32_t* __restrict__ long_visit,
@@ -405,11 +419,11 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
                 const int q = qb + q0;
                 const bool active = q < kq;
                 const int64_t o = j * k + (active ? q : 0);  // lane's positions: o + c * kq
-                int64_t my[VEC];
+                int32_t my[VEC];
                 float acc[VEC];
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) {
-                    my[c] = (int64_t)sp_index[o + c * kq];
+                    my[c] = (int32_t)sp_index[o + c * kq];
                     acc[c] = 0.f;
                 }
                 for (int p0 = b; p0 < e; p0 += G * 4) {
@@ -419,11 +433,11 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
                         const int p = p0 + u * G + g;
                         const bool ok = p < e;
                         const int pc = ok ? p : b;
-                        const float* __restrict__ row = dY + (int64_t)slab_src[pc] * dim;
+                        const int32_t row = slab_src[pc];
                         a[u] = ok ? slab_val[pc] : 0.f;
 #pragma unroll
                         for (int c = 0; c < VEC; ++c) {
-                            const float x = row[my[c]];
+                            const float x = load_sampled<OFF32>(dY, row, dim, my[c]);
                             gv[u][c] = ok ? x : 0.f;
                         }
                     }
@@ -459,11 +473,11 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
         if (have && e - b <= kSlabLongVisit) {
             for (int q = q0; q < kq; q += LPD) {  // one pass unless k / VEC > 64
                 const int64_t o = j * k + q;  // lane's positions: o + c * kq
-                int64_t my[VEC];
+                int32_t my[VEC];
                 float acc[VEC];
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) {
-                    my[c] = (int64_t)sp_index[o + c * kq];
+                    my[c] = (int32_t)sp_index[o + c * kq];
                     acc[c] = dXs[o + c * kq];
                 }
                 int p = b;
@@ -471,10 +485,10 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
                     float gv[4][VEC], a[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const float* __restrict__ row = dY + (int64_t)slab_src[p + u] * dim;
+                        const int32_t row = slab_src[p + u];
                         a[u] = slab_val[p + u];
 #pragma unroll
-                        for (int c = 0; c < VEC; ++c) gv[u][c] = row[my[c]];
+                        for (int c = 0; c < VEC; ++c) gv[u][c] = load_sampled<OFF32>(dY, row, dim, my[c]);
                     }
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
@@ -487,11 +501,11 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
                     for (int u = 0; u < 3; ++u) {
                         const bool ok = p + u < e;
                         const int pc = ok ? p + u : b;
-                        const float* __restrict__ row = dY + (int64_t)slab_src[pc] * dim;
+                        const int32_t row = slab_src[pc];
                         a[u] = ok ? slab_val[pc] : 0.f;
 #pragma unroll
                         for (int c = 0; c < VEC; ++c) {
-                            const float x = row[my[c]];
+                            const float x = load_sampled<OFF32>(dY, row, dim, my[c]);
                             gv[u][c] = ok ? x : 0.f;
                         }
                     }
@@ -508,7 +522,7 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
     }
 }
 
-template <int VEC, typename IdxT>
+template <int VEC, bool OFF32, typename IdxT>
 maxk_status launch_slab_t(const SlabSet& S, const float* dY, const IdxT* sp_index, int dim, int k, float* dXs,
                           hipStream_t s)
 {
@@ -522,7 +536,7 @@ maxk_status launch_slab_t(const SlabSet& S, const float* dY, const IdxT* sp_inde
     do {                                                                                                           \
         const int64_t tasks = (ve - vb + (kWave / LPD) - 1) / (kWave / LPD);                                       \
         const unsigned grid = (unsigned)std::min<int64_t>(tasks, 256 * 32);                                        \
-        hipLaunchKernelGGL((bwd_slab_kernel<VEC, LPD, IdxT>), dim3(grid + (unsigned)nlb), dim3(kWave), 0, s,      \
+        hipLaunchKernelGGL((bwd_slab_kernel<VEC, LPD, OFF32, IdxT>), dim3(grid + (unsigned)nlb), dim3(kWave), 0, s,      \
                            S.d_visit_node, S.d_visit_begin, vb, ve, S.d_long_visit, lb, le, nlb, S.d_src, S.d_val, \
                            dY, sp_index, dim, k, dXs);                                                             \
     } while (0)
@@ -540,11 +554,15 @@ maxk_status launch_slab_t(const SlabSet& S, const float* dY, const IdxT* sp_inde
 }
 
 template <typename IdxT>
-maxk_status launch_slab_i(const SlabSet& S, const float* dY, const IdxT* sp_index, int dim, int k, float* dXs,
-                          hipStream_t s)
+maxk_status launch_slab_i(const SlabSet& S, const float* dY, const IdxT* sp_index, int64_t N, int dim, int k,
+                          float* dXs, hipStream_t s)
 {
-    return (k % 4 == 0) ? launch_slab_t<4>(S, dY, sp_index, dim, k, dXs, s)
-                        : launch_slab_t<1>(S, dY, sp_index, dim, k, dXs, s);
+    const bool off32 = N * (int64_t)dim * 4 <= 0xFFFFFFFFll;
+    if (k % 4 == 0)
+        return off32 ? launch_slab_t<4, true>(S, dY, sp_index, dim, k, dXs, s)
+                     : launch_slab_t<4, false>(S, dY, sp_index, dim, k, dXs, s);
+    return off32 ? launch_slab_t<1, true>(S, dY, sp_index, dim, k, dXs, s)
+                 : launch_slab_t<1, false>(S, dY, sp_index, dim, k, dXs, s);
 }
 
 template <typename IdxT>
@@ -661,9 +679,9 @@ maxk_status launch_bwd_slab_pull(const SlabSet& S, const float* dY, const void* 
 {
     maxk_status st = launch_fill_zero(dXs, N * (int64_t)k, s);
     if (st != MAXK_OK || S.n_visits == 0) return st;
-    if (index_bytes == 1) return launch_slab_i(S, dY, (const uint8_t*)sp_index, dim, k, dXs, s);
-    if (index_bytes == 2) return launch_slab_i(S, dY, (const uint16_t*)sp_index, dim, k, dXs, s);
-    return launch_slab_i(S, dY, (const int32_t*)sp_index, dim, k, dXs, s);
+    if (index_bytes == 1) return launch_slab_i(S, dY, (const uint8_t*)sp_index, N, dim, k, dXs, s);
+    if (index_bytes == 2) return launch_slab_i(S, dY, (const uint16_t*)sp_index, N, dim, k, dXs, s);
+    return launch_slab_i(S, dY, (const int32_t*)sp_index, N, dim, k, dXs, s);
 }
 
 }  // namespace maxk
