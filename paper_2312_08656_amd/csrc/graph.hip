@@ -484,9 +484,11 @@ int auto_bwd_mode(const maxk_graph* g, int dim, int k)
     const double n_slabs = std::ceil((double)g->N / slab_rows_for(dim));
     const double entries_per_visit = (double)g->nnz / std::max(1.0, (double)g->N * n_slabs);
     if (entries_per_visit >= 2.0 && n_slabs * (double)g->N < 1.8e19) return MAXK_BWD_SLAB_PULL;
-    const double lines = (dim / 32.0) * (1.0 - std::pow(1.0 - 32.0 / dim, (double)k));  // expected lines touched
-    const double pull_cost = (dim <= 32 ? 1.0 : lines) * 128.0 / 8.5;                  // bytes / (TB/s)
-    const double expand_cost = 8.0 * k / 4.3;
+    // expected cache lines of a dY row touched by k sorted columns; measured crossover on four graphs:
+    // expand/reduce (8k bytes per entry) beats pull (lines * 128 bytes per entry) while 8k < 44 * lines
+    const double lines = dim <= 32 ? 1.0 : (dim / 32.0) * (1.0 - std::pow(1.0 - 32.0 / dim, (double)k));
+    const double pull_cost = lines * 128.0 / 2.9;
+    const double expand_cost = 8.0 * k;
     const bool fits = (double)g->nnz * k * 4.0 <= 96e9;
     return (fits && expand_cost < pull_cost) ? MAXK_BWD_EXPAND_REDUCE : MAXK_BWD_PULL_CSC;
 }

@@ -91,14 +91,18 @@ __global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict_
         }
     }
 
-    // k-th largest key by MSB-first descent; `exact` = the prefix already keeps exactly k
+    // k-th largest key by MSB-first descent; `exact` = the prefix already keeps exactly k.
+    // Everything but the compares is wave-uniform; readfirstlane tells the compiler so, which keeps
+    // the prefix, the candidate and the counts in scalar registers (4 vector compares per step).
     uint32_t prefix = 0u;
     bool exact = false;
+#pragma unroll
     for (int bit = 31; bit >= 0; --bit) {
         const uint32_t cand = prefix | (1u << bit);
         int cnt = 0;
 #pragma unroll
         for (int e = 0; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= cand));
+        cnt = __builtin_amdgcn_readfirstlane(cnt);
         if (cnt >= k) {
             prefix = cand;
             if (cnt == k) { exact = true; break; }
