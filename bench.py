@@ -29,6 +29,15 @@ if str(ROOT) not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
+# L2 <-> fabric bytes per API call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what a plain
+# 1 GiB copy reads on the same counters: x2.0 and x1.0), from profiles/dense_k32_step_trace_and_counters.txt.
+# Keyed by (workload, k, entry point, backward mode); anything else reports null.
+MEASURED_TRAFFIC_BYTES = {
+    ("dense", 32, "maxk_spgemm_fwd", None): 22.97e9,
+    ("dense", 32, "maxk_sspmm_bwd", "auto"): 12.95e9,
+    ("dense", 32, "maxk_sspmm_bwd", "slab"): 12.95e9,
+}
+
 
 def algorithmic_bytes(N: int, nnz: int, dim: int, k: int, index_bytes: int = 1) -> dict:
     """Bytes each operator must move, from the paper's traffic model (Sec. 4.3) plus the
@@ -154,8 +163,9 @@ def main() -> int:
     dom_name, dom_ms, dom_bytes = max((("maxk_spgemm_fwd", t_fwd, ab["fwd"]), ("maxk_sspmm_bwd", t_bwd, ab["bwd"])),
                                       key=lambda t: t[1])
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, k0, dom_name, args.bwd_mode if "bwd" in dom_name else None))
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": round(dom_ms, 4)}
 
     if args.calibrate_copy:
