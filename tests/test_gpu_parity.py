@@ -196,6 +196,26 @@ def test_outputs_are_overwritten_and_calls_repeat():
 # ------------------------------------------------------------------ mid size, element by element
 
 
+@pytest.mark.parametrize("aggregator", ["mean", "gin_sum"])
+def test_other_aggregators_as_edge_weights(aggregator):
+    # "A could have different expressions according to aggregator type" (Sec. 3.2): GraphSAGE's mean
+    # aggregator is val = 1/d_i (a non-symmetric matrix on a symmetric structure), a GIN-style sum is
+    # val = 1 with (1 + eps) on the diagonal (unnormalised magnitudes against the error bound)
+    g0 = synth.graph("sparse_mid")
+    if aggregator == "mean":
+        val = synth.make_weights(g0, "mean")
+    else:
+        val = np.ones(g0.nnz, dtype=np.float32)
+        rows = np.repeat(np.arange(g0.N, dtype=np.int64), np.diff(g0.rowptr))
+        val[rows == g0.col] = np.float32(1.0 + 0.1)
+    g = synth.Graph(g0.N, g0.rowptr, g0.col, val, dict(g0.meta))
+    dg = DeviceGraph(g)
+    H, dY = synth.features("sparse_mid", "H"), synth.features("sparse_mid", "dY")
+    full_pass(dg, H, dY, 32, 1, sampled=False, spmm=True)
+    dg.close()
+
+
+
 def test_sparse_mid_full_compare():
     name = "sparse_mid"
     cfg = synth.CONFIGS[name]
