@@ -128,6 +128,14 @@ MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void
                            int32_t dim, int32_t k, float* d_dXs, void* stream);
 
 /*
+ * MaxK backward (Sec. 3.1 definition, part (ii): the gradient keeps the sparsity pattern of the
+ * forward pass): d_dense[i, sp_index[i,t]] = d_values[i,t], every other entry of d_dense[N x dim] = 0.
+ * d_values is fp32 [N x k] (the dXs of maxk_sspmm_bwd).  Columns of a row must be distinct.
+ */
+MAXK_API maxk_status maxk_cbsr_scatter(const float* d_values, const void* d_sp_index, int32_t index_bytes, int64_t N,
+                                       int32_t dim, int32_t k, float* d_dense, void* stream);
+
+/*
  * Dense-feature SpMM Y = A * H on the same graph handle: the operator the paper
  * measures its speedups against (Sec. 5.2), here as a same-GPU baseline.
  */

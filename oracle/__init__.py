@@ -12,6 +12,7 @@ Functions take and return NumPy arrays:
     spgemm_fwd(rowptr, col, val, sp_data, sp_index, dim, rows=None) -> Y f64, Yabs f64
     sspmm_bwd(rowptr, col, val, dY, sp_index, nodes=None)           -> D f64, Dabs f64
     spmm(rowptr, col, val, H, rows=None)                            -> Y f64, Yabs f64
+    cbsr_scatter(dXs, sp_index, dim)                                -> dH f32 [N,dim]
 
 ``rows`` / ``nodes`` restrict the outputs to a sample (full-size parity checks
 compute sampled outputs one by one).  The ``*abs`` arrays hold, per output
@@ -58,6 +59,8 @@ def _load():
     lib.oracle_spmm.restype = ctypes.c_int
     lib.oracle_sspmm_bwd.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, vp, i64, i64, i64, vp, vp]
     lib.oracle_sspmm_bwd.restype = ctypes.c_int
+    lib.oracle_cbsr_scatter.argtypes = [vp, vp, i64, i32, i32, vp]
+    lib.oracle_cbsr_scatter.restype = ctypes.c_int
     lib.oracle_num_threads.argtypes = []
     lib.oracle_num_threads.restype = i32
     _lib = lib
@@ -127,6 +130,18 @@ def spmm(rowptr, col, val, H, rows=None):
     if rc != 0:
         raise ValueError("oracle_spmm: bad arguments")
     return Y, Yabs
+
+
+def cbsr_scatter(dXs, sp_index, dim: int):
+    """MaxK backward: dense dH with dXs placed at the CBSR columns, zeros elsewhere (Sec. 3.1 definition (ii))."""
+    dXs, sp_index = _c(dXs, np.float32), _c(sp_index, np.int32)
+    N, k = dXs.shape
+    assert sp_index.shape == (N, k)
+    dH = np.empty((N, dim), dtype=np.float32)
+    rc = _load().oracle_cbsr_scatter(_p(dXs), _p(sp_index), N, dim, k, _p(dH))
+    if rc != 0:
+        raise ValueError("oracle_cbsr_scatter: bad arguments")
+    return dH
 
 
 def sspmm_bwd(rowptr, col, val, dY, sp_index, nodes=None, src_range=None):

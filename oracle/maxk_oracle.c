@@ -11,6 +11,7 @@
  *   oracle_spgemm_fwd  X_l[i,:] = sum_j A[i,j] * h(X)[j,:]   (Eq. 2 left; Sec. 3.2 row-wise product)
  *   oracle_sspmm_bwd   dXs = (A^T * dX_l) at sp_index        (Eq. 2 right, Eq. 3; Alg. 2 with destination row j)
  *   oracle_spmm        Y = A * H, dense features             (the SpMM the paper compares against, Sec. 5.2)
+ *   oracle_cbsr_scatter dH from dXs: MaxK's backward          (Sec. 3.1 definition, part (ii))
  *
  * Readings of points the paper leaves open (each restated where it is used):
  *   - top-k is by signed value, exactly k survive, ties at the k-th value go
@@ -191,6 +192,19 @@ int oracle_sspmm_bwd(int64_t N, const int32_t *rowptr, const int32_t *col, const
             }
         }
     }
+    return 0;
+}
+
+/*
+ * MaxK backward (Sec. 3.1 definition, part (ii): the gradient keeps the forward sparsity pattern):
+ * dH[i, sp_index[i,t]] = dXs[i,t], every other entry of dH is zero.  Pure placement, no arithmetic.
+ */
+int oracle_cbsr_scatter(const float *dXs, const int32_t *sp_index, int64_t N, int32_t dim, int32_t k, float *dH)
+{
+    if (N < 0 || dim < 1 || k < 1 || k > dim) return -1;
+    memset(dH, 0, sizeof(float) * (size_t)(N * dim));
+    for (int64_t i = 0; i < N; ++i)
+        for (int32_t t = 0; t < k; ++t) dH[i * (int64_t)dim + sp_index[i * (int64_t)k + t]] = dXs[i * (int64_t)k + t];
     return 0;
 }
 

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     index_dtype,
     lib_path,
     load_library,
+    maxk_cbsr_scatter,
     maxk_graph_create,
     maxk_graph_destroy,
     maxk_spgemm_fwd,
@@ -24,3 +25,4 @@ from .binding import (  # noqa: F401
     maxk_topk_cbsr,
     spmm_baseline,
 )
+from .autograd import MaxKAggregate, maxk_aggregate  # noqa: E402,F401

@@ -14,7 +14,7 @@ BWD_AUTO, BWD_PULL_CSC, BWD_PUSH_CSR, BWD_EXPAND_REDUCE, BWD_SLAB_PULL = 0, 1, 2
 
 EXPORTS = (
     "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode", "maxk_graph_info",
-    "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_sspmm_bwd", "spmm_baseline", "maxk_status_string",
+    "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_sspmm_bwd", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
     "maxk_last_hip_error", "maxk_version",
 )
 
@@ -45,9 +45,11 @@ def load_library() -> ctypes.CDLL:
     lib.maxk_topk_cbsr.argtypes = [vp, i64, i32, i32, vp, vp, i32, vp]
     lib.maxk_spgemm_fwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     lib.maxk_sspmm_bwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.maxk_cbsr_scatter.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp]
     lib.spmm_baseline.argtypes = [vp, vp, i32, vp, vp]
     for name in ("maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode",
-                 "maxk_graph_info", "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_sspmm_bwd", "spmm_baseline",
+                 "maxk_graph_info", "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_sspmm_bwd", "maxk_cbsr_scatter",
+                 "spmm_baseline",
                  "maxk_last_hip_error", "maxk_version"):
         getattr(lib, name).restype = i32
     lib.maxk_status_string.argtypes = [i32]
@@ -166,6 +168,18 @@ def maxk_sspmm_bwd(g: MaxKGraph, dY: torch.Tensor, sp_index: torch.Tensor, dXs: 
     _check(load_library().maxk_sspmm_bwd(g.handle, _dev(dY, torch.float32, "dY"),
                                          _dev(sp_index, sp_index.dtype, "sp_index"), ib, dim, k,
                                          _dev(dXs, torch.float32, "dXs"), _stream()), "maxk_sspmm_bwd")
+
+
+def maxk_cbsr_scatter(values: torch.Tensor, sp_index: torch.Tensor, dense: torch.Tensor) -> None:
+    """dense [N,dim] fp32 is overwritten: values [N,k] placed at the CBSR columns, zeros elsewhere."""
+    N, k = values.shape
+    dim = dense.shape[1]
+    if tuple(sp_index.shape) != (N, k) or dense.shape[0] != N:
+        raise MaxKError("maxk_cbsr_scatter: shape mismatch")
+    ib = _INDEX_BYTES[sp_index.dtype]
+    _check(load_library().maxk_cbsr_scatter(_dev(values, torch.float32, "values"),
+                                            _dev(sp_index, sp_index.dtype, "sp_index"), ib, N, dim, k,
+                                            _dev(dense, torch.float32, "dense"), _stream()), "maxk_cbsr_scatter")
 
 
 def spmm_baseline(g: MaxKGraph, H: torch.Tensor, Y: torch.Tensor) -> None:

@@ -84,6 +84,9 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 maxk_status launch_topk(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
                         hipStream_t s);
 
+maxk_status launch_cbsr_scatter(const float* values, const void* sp_index, int index_bytes, int64_t N, int dim, int k,
+                                float* dense, hipStream_t s);
+
 // `packed`: workspace of N * fwd_packed_record_bytes(k, index_bytes) bytes to use the packed-record path, or null
 maxk_status launch_spgemm_fwd(const ItemList& items, const int32_t* col, const float* val, const float* sp_data,
                               const void* sp_index, int index_bytes, int64_t N, char* packed, int dim, int k,

@@ -688,6 +688,19 @@ MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void
                            (hipStream_t)stream);
 }
 
+MAXK_API maxk_status maxk_cbsr_scatter(const float* d_values, const void* d_sp_index, int32_t index_bytes, int64_t N,
+                                       int32_t dim, int32_t k, float* d_dense, void* stream)
+{
+    if (N < 0 || dim < 1 || k < 1 || k > dim || bad_index_bytes(index_bytes, dim)) return MAXK_INVALID_ARGUMENT;
+    if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
+    if (N > 0x7FFFFFF0ll) return MAXK_INVALID_ARGUMENT;
+    if (N == 0) return MAXK_OK;
+    if (!d_values || !d_sp_index || !d_dense) return MAXK_INVALID_ARGUMENT;
+    if (!aligned(d_values, 4) || !aligned(d_dense, 4) || !aligned(d_sp_index, (size_t)index_bytes))
+        return MAXK_INVALID_ARGUMENT;
+    return launch_cbsr_scatter(d_values, d_sp_index, index_bytes, N, dim, k, d_dense, (hipStream_t)stream);
+}
+
 MAXK_API maxk_status spmm_baseline(maxk_graph* g, const float* d_H, int32_t dim, float* d_Y, void* stream)
 {
     if (!g || dim < 1) return MAXK_INVALID_ARGUMENT;

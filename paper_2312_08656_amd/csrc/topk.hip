@@ -143,6 +143,28 @@ __global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict_
     }
 }
 
+// MaxK backward: dense[row, sp_index[row,t]] = values[row,t], zeros elsewhere.  One wavefront per row;
+// the row is assembled in LDS so that it leaves the CU as one coalesced write.
+template <typename IdxT>
+__global__ __launch_bounds__(256) void cbsr_scatter_kernel(const float* __restrict__ values,
+                                                           const IdxT* __restrict__ sp_index, int64_t N, int dim,
+                                                           int k, float* __restrict__ dense)
+{
+    extern __shared__ float rows[];  // 4 rows of dim floats
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+    const int64_t row = (int64_t)blockIdx.x * 4 + w;
+    float* __restrict__ buf = rows + w * dim;
+    for (int c = lane; c < dim; c += kWave) buf[c] = 0.f;
+    __syncthreads();
+    if (row < N)
+        for (int t = lane; t < k; t += kWave) buf[(int)sp_index[row * (int64_t)k + t]] = values[row * (int64_t)k + t];
+    __syncthreads();
+    if (row < N) {
+        float* __restrict__ out = dense + row * (int64_t)dim;
+        for (int c = lane; c < dim; c += kWave) out[c] = buf[c];
+    }
+}
+
 template <int E, int V>
 maxk_status launch_e(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
                      hipStream_t s)
@@ -161,6 +183,21 @@ maxk_status launch_e(const float* H, int64_t N, int dim, int k, float* sp_data, 
 }
 
 }  // namespace
+
+maxk_status launch_cbsr_scatter(const float* values, const void* sp_index, int index_bytes, int64_t N, int dim, int k,
+                                float* dense, hipStream_t s)
+{
+    if (N == 0) return MAXK_OK;
+    const int64_t blocks = (N + 3) / 4;
+    if (blocks > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
+    dim3 grid((unsigned)blocks), block(4 * kWave);
+    const size_t lds = sizeof(float) * 4 * (size_t)dim;
+    if (index_bytes == 1) hipLaunchKernelGGL((cbsr_scatter_kernel<uint8_t>), grid, block, lds, s, values, (const uint8_t*)sp_index, N, dim, k, dense);
+    else if (index_bytes == 2) hipLaunchKernelGGL((cbsr_scatter_kernel<uint16_t>), grid, block, lds, s, values, (const uint16_t*)sp_index, N, dim, k, dense);
+    else hipLaunchKernelGGL((cbsr_scatter_kernel<int32_t>), grid, block, lds, s, values, (const int32_t*)sp_index, N, dim, k, dense);
+    MAXK_LAUNCH_CHECK();
+    return MAXK_OK;
+}
 
 maxk_status launch_topk(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
                         hipStream_t s)

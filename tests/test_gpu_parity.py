@@ -228,3 +228,43 @@ def test_sparse_mid_full_compare():
         say(f"  {name} k={k}")
         full_pass(dg, H, dY, k, cfg.index_bytes, sampled=False, spmm=(k == cfg.ks[0]))
     dg.close()
+
+
+# ------------------------------------------------------------------ MaxK backward scatter and autograd glue
+
+
+@pytest.mark.parametrize("dim,k,ib", [(64, 8, 1), (384, 96, 2), (37, 5, 4), (256, 256, 1)])
+def test_cbsr_scatter_is_exact(dim, k, ib):
+    N = 3001
+    H = synth.normal_matrix(N, dim, 12)
+    vals = synth.normal_matrix(N, k, 13)
+    _, ri = oracle.topk_cbsr(H, k)
+    idx_np = ri.astype({1: np.uint8, 2: np.uint16, 4: np.int32}[ib])
+    idx_dev = torch.from_numpy(idx_np.view(np.int16) if ib == 2 else idx_np).cuda()
+    if ib == 2:
+        idx_dev = idx_dev.view(torch.uint16)
+    dense = torch.full((N, dim), float("nan"), device="cuda")
+    maxk.maxk_cbsr_scatter(to_dev(vals), idx_dev, dense)
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), oracle.cbsr_scatter(vals, ri, dim).view(np.uint32))
+
+
+def test_autograd_function_matches_the_oracle_chain():
+    name = "tiny_directed"
+    g = synth.graph(name)
+    cfg = synth.CONFIGS[name]
+    H, dY = synth.features(name, "H"), synth.features(name, "dY")
+    dg = DeviceGraph(g)
+    for k in (8, 20):
+        Hd = to_dev(H).requires_grad_(True)
+        Y = maxk.maxk_aggregate(Hd, dg.handle, k)
+        Y.backward(to_dev(dY))
+        rd, ri = oracle.topk_cbsr(H, k)
+        ref, refabs = oracle.spgemm_fwd(g.rowptr, g.col, g.val, rd, ri, cfg.dim)
+        assert (np.abs(Y.detach().cpu().numpy() - ref) <= 1e-5 * refabs + 1e-6).all()
+        D, Dabs = oracle.sspmm_bwd(g.rowptr, g.col, g.val, dY, ri)
+        want = oracle.cbsr_scatter(D.astype(np.float32), ri, cfg.dim)
+        bound = oracle.cbsr_scatter((1e-5 * Dabs + 1e-6).astype(np.float32), ri, cfg.dim) + 1e-7
+        got = Hd.grad.cpu().numpy()
+        assert (np.abs(got - want) <= bound).all()
+        assert ((got != 0).sum(axis=1) <= k).all()
+    dg.close()

@@ -162,3 +162,30 @@ def test_row_and_node_sampling_agree_with_full_result():
     Hs, _ = oracle.spmm(g.rowptr, g.col, g.val, H, rows=rows)
     Hf, _ = oracle.spmm(g.rowptr, g.col, g.val, H)
     assert np.array_equal(Hs, Hf[rows])
+
+
+def test_cbsr_scatter_and_the_whole_backward_chain_against_torch_autograd():
+    # MaxK's backward keeps the forward pattern (Sec. 3.1 definition (ii)): with X = H * mask,
+    # Y = A X and L = <Y, dY>, plain PyTorch autograd on dense CPU tensors gives dL/dH = (A^T dY) * mask.
+    import torch
+    g = synth.make_graph(60, 500, 0, directed=True, seed=21, weights="normal")
+    dim, k = 24, 7
+    H = synth.normal_matrix(g.N, dim, 8)
+    dY = synth.normal_matrix(g.N, dim, 9)
+    sp_data, sp_index = oracle.topk_cbsr(H, k)
+    D, _ = oracle.sspmm_bwd(g.rowptr, g.col, g.val, dY, sp_index)
+    dH = oracle.cbsr_scatter(D.astype(np.float32), sp_index, dim)
+    # placement alone, against NumPy
+    want = np.zeros((g.N, dim), dtype=np.float32)
+    np.put_along_axis(want, sp_index.astype(np.int64), D.astype(np.float32), axis=1)
+    assert np.array_equal(dH, want)
+    assert ((dH != 0).sum(axis=1) <= k).all()
+    # the chain, against autograd
+    order = np.argsort(-H, axis=1, kind="stable")[:, :k]
+    mask = np.zeros((g.N, dim), dtype=np.float64)
+    np.put_along_axis(mask, order, 1.0, axis=1)
+    A = torch.from_numpy(dense_from_csr(g.rowptr, g.col, g.val, g.N))
+    Ht = torch.from_numpy(H.astype(np.float64)).requires_grad_(True)
+    Y = A @ (Ht * torch.from_numpy(mask))
+    (Y * torch.from_numpy(dY.astype(np.float64))).sum().backward()
+    np.testing.assert_allclose(dH, Ht.grad.numpy(), rtol=0, atol=2e-6)
