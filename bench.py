@@ -213,7 +213,8 @@ def main() -> int:
                             f"{tag}_speedup_vs_spmm": round(spmm_ms / tb, 2)})
             gr.set_bwd_mode(maxk.BWD_AUTO)
             tb, _ = timeit(lambda: maxk.maxk_sspmm_bwd(gr, dYd, si, dx), args.sweep_reps, warm=1)
-            row.update({"bwd_ms": round(tb, 4), "bwd_edges_k_per_s": nnz * k / (tb * 1e-3),
+            row.update({"bwd_auto_kernel": gr.bwd_choice(dim, k),
+                        "bwd_ms": round(tb, 4), "bwd_edges_k_per_s": nnz * k / (tb * 1e-3),
                         "bwd_hbm_frac": round(b["bwd"] / (tb * 1e-3) / 8e12, 4),
                         "bwd_speedup_vs_spmm": round(spmm_ms / tb, 2),
                         "fwd_bwd_edges_k_per_s": 2.0 * nnz * k / ((tf + tb) * 1e-3)})
@@ -256,7 +257,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: R-MAT graph N={N} nnz={nnz} (stands for: {cfg.stands_for}), "
                                f"dim={dim}, k={k0}, uint{8 * ib} sp_index, GCN weights, H,dY~N(0,1)",
                    "N": N, "nnz": nnz, "dim": dim, "k": k0, "max_degree": g.meta.get("max_degree"),
-                   "bwd_mode": args.bwd_mode,
+                   "bwd_mode": args.bwd_mode, "bwd_kernel": gr.bwd_choice(dim, k0),
                    "graph_handle": gr.info()},
         "step_breakdown_ms": {"topk_cbsr": round(t_topk, 4), "spgemm_fwd": round(t_fwd, 4),
                               "sspmm_bwd": round(t_bwd, 4)},

@@ -94,6 +94,10 @@ MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k);
 /* Selects the backward kernel (MAXK_BWD_*). */
 MAXK_API maxk_status maxk_graph_set_bwd_mode(maxk_graph* g, int32_t mode);
 
+/* The MAXK_BWD_* kernel maxk_sspmm_bwd would run for (dim, k) with the handle's current mode
+ * (resolves MAXK_BWD_AUTO); negative maxk_status on bad arguments. */
+MAXK_API int32_t maxk_graph_bwd_choice(const maxk_graph* g, int32_t dim, int32_t k);
+
 /* Reads back sizes: any out pointer may be NULL. */
 MAXK_API maxk_status maxk_graph_info(const maxk_graph* g, int64_t* N, int64_t* nnz, int64_t* n_fwd_items,
                             int64_t* n_split_rows, int64_t* max_degree, int64_t* workspace_bytes);

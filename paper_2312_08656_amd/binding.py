@@ -13,7 +13,8 @@ _LIB: Optional[ctypes.CDLL] = None
 BWD_AUTO, BWD_PULL_CSC, BWD_PUSH_CSR, BWD_EXPAND_REDUCE, BWD_SLAB_PULL = 0, 1, 2, 3, 4
 
 EXPORTS = (
-    "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode", "maxk_graph_info",
+    "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode", "maxk_graph_bwd_choice",
+    "maxk_graph_info",
     "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_sspmm_bwd", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
     "maxk_last_hip_error", "maxk_version",
 )
@@ -41,6 +42,8 @@ def load_library() -> ctypes.CDLL:
     lib.maxk_graph_destroy.argtypes = [vp]
     lib.maxk_graph_reserve.argtypes = [vp, i32, i32]
     lib.maxk_graph_set_bwd_mode.argtypes = [vp, i32]
+    lib.maxk_graph_bwd_choice.argtypes = [vp, i32, i32]
+    lib.maxk_graph_bwd_choice.restype = i32
     lib.maxk_graph_info.argtypes = [vp] + [ctypes.POINTER(i64)] * 6
     lib.maxk_topk_cbsr.argtypes = [vp, i64, i32, i32, vp, vp, i32, vp]
     lib.maxk_spgemm_fwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
@@ -109,6 +112,14 @@ class MaxKGraph:
 
     def set_bwd_mode(self, mode: int) -> None:
         _check(load_library().maxk_graph_set_bwd_mode(self.handle, mode), "maxk_graph_set_bwd_mode")
+
+    def bwd_choice(self, dim: int, k: int) -> str:
+        """Name of the backward kernel maxk_sspmm_bwd would run for (dim, k)."""
+        c = load_library().maxk_graph_bwd_choice(self.handle, dim, k)
+        if c < 0:
+            _check(c, "maxk_graph_bwd_choice")
+        return {BWD_PULL_CSC: "pull", BWD_PUSH_CSR: "push", BWD_EXPAND_REDUCE: "expand_reduce",
+                BWD_SLAB_PULL: "slab_pull"}[c]
 
     def info(self) -> dict:
         vals = [ctypes.c_int64() for _ in range(6)]

@@ -608,6 +608,12 @@ MAXK_API maxk_status maxk_graph_set_bwd_mode(maxk_graph* g, int32_t mode)
     return MAXK_OK;
 }
 
+MAXK_API int32_t maxk_graph_bwd_choice(const maxk_graph* g, int32_t dim, int32_t k)
+{
+    if (!g || dim < 1 || k < 1 || k > dim) return MAXK_INVALID_ARGUMENT;
+    return g->bwd_mode == MAXK_BWD_AUTO ? auto_bwd_mode(g, dim, k) : g->bwd_mode;
+}
+
 MAXK_API maxk_status maxk_graph_info(const maxk_graph* g, int64_t* N, int64_t* nnz, int64_t* n_fwd_items, int64_t* n_split_rows,
                             int64_t* max_degree, int64_t* workspace_bytes)
 {

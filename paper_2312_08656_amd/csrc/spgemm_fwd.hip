@@ -29,59 +29,17 @@
 namespace maxk {
 namespace {
 
-template <typename IdxT, int VEC>
-struct IdxVec;
-template <>
-struct IdxVec<uint8_t, 4> {
-    uint32_t w;
-    __device__ __forceinline__ void load(const uint8_t* p) { w = *reinterpret_cast<const uint32_t*>(p); }
-    __device__ __forceinline__ int get(int i) const { return (w >> (8 * i)) & 0xFFu; }
-};
-template <>
-struct IdxVec<uint16_t, 4> {
-    uint2 w;
-    __device__ __forceinline__ void load(const uint16_t* p) { w = *reinterpret_cast<const uint2*>(p); }
-    __device__ __forceinline__ int get(int i) const { return ((i < 2 ? w.x : w.y) >> (16 * (i & 1))) & 0xFFFFu; }
-};
-template <>
-struct IdxVec<int32_t, 4> {
-    int4 w;
-    __device__ __forceinline__ void load(const int32_t* p) { w = *reinterpret_cast<const int4*>(p); }
-    __device__ __forceinline__ int get(int i) const { return i == 0 ? w.x : i == 1 ? w.y : i == 2 ? w.z : w.w; }
-};
+constexpr int kRounds = 4;  // unit rounds in flight per wavefront (fallback kernel)
+
+// Fallback for shapes whose private copies would not fit in LDS: a single copy of the output row,
+// updated with LDS floating-point atomics (slow on this chip, see the header comment).
 template <typename IdxT>
-struct IdxVec<IdxT, 1> {
-    int w;
-    __device__ __forceinline__ void load(const IdxT* p) { w = (int)*p; }
-    __device__ __forceinline__ int get(int) const { return w; }
-};
-
-template <int VEC>
-struct ValVec;
-template <>
-struct ValVec<4> {
-    float4 w;
-    __device__ __forceinline__ void load(const float* p) { w = *reinterpret_cast<const float4*>(p); }
-    __device__ __forceinline__ float get(int i) const { return i == 0 ? w.x : i == 1 ? w.y : i == 2 ? w.z : w.w; }
-};
-template <>
-struct ValVec<1> {
-    float w;
-    __device__ __forceinline__ void load(const float* p) { w = *p; }
-    __device__ __forceinline__ float get(int) const { return w; }
-};
-
-constexpr int kRounds = 4;  // unit rounds in flight per wavefront
-
-// VEC: CBSR entries per unit (4 when k % 4 == 0 and pointers are 16-byte aligned, else 1)
-// KU : units per stored entry (k / VEC) when known at compile time, 0 = runtime
-template <int VEC, int KU, typename IdxT>
-__global__ __launch_bounds__(kWave) void spgemm_fwd_kernel(const WorkItem* __restrict__ items,
-                                                           const int32_t* __restrict__ col,
-                                                           const float* __restrict__ val,
-                                                           const float* __restrict__ sp_data,
-                                                           const IdxT* __restrict__ sp_index, int dim, int k, int ku_rt,
-                                                           float* __restrict__ Y, float* __restrict__ partials)
+__global__ __launch_bounds__(kWave) void spgemm_fwd_atomic_kernel(const WorkItem* __restrict__ items,
+                                                                  const int32_t* __restrict__ col,
+                                                                  const float* __restrict__ val,
+                                                                  const float* __restrict__ sp_data,
+                                                                  const IdxT* __restrict__ sp_index, int dim, int k,
+                                                                  float* __restrict__ Y, float* __restrict__ partials)
 {
     extern __shared__ float row_buf[];
     const int lane = threadIdx.x;
@@ -89,7 +47,6 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_kernel(const WorkItem* __res
     for (int c = lane; c < dim; c += kWave) row_buf[c] = 0.f;
     __syncthreads();
 
-    const int ku = KU ? KU : ku_rt;
     for (int base = it.begin; base < it.end; base += kWave) {
         const int n = min(kWave, it.end - base);
         int my_col = 0;
@@ -98,43 +55,33 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_kernel(const WorkItem* __res
             my_col = col[base + lane];
             my_val = val[base + lane];
         }
-        const int units = n * ku;
+        const int units = n * k;
         for (int u0 = 0; u0 < units; u0 += kWave * kRounds) {
-            ValVec<VEC> d[kRounds];
-            IdxVec<IdxT, VEC> ix[kRounds];
-            float a[kRounds];
+            float d[kRounds], a[kRounds];
+            int ix[kRounds];
             bool ok[kRounds];
 #pragma unroll
             for (int r = 0; r < kRounds; ++r) {
                 const int u = u0 + r * kWave + lane;
                 ok[r] = u < units;
                 const int uc = ok[r] ? u : 0;
-                const int e = uc / ku;
-                const int q = uc - e * ku;
+                const int e = uc / k;
+                const int t = uc - e * k;
                 const int c = __shfl(my_col, e);
                 a[r] = __shfl(my_val, e);
-                const int64_t off = (int64_t)c * k + q * VEC;
-                d[r].load(sp_data + off);
-                ix[r].load(sp_index + off);
+                const int64_t off = (int64_t)c * k + t;
+                d[r] = sp_data[off];
+                ix[r] = (int)sp_index[off];
             }
 #pragma unroll
-            for (int r = 0; r < kRounds; ++r) {
-                if (ok[r]) {
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) atomicAdd(&row_buf[ix[r].get(j)], a[r] * d[r].get(j));
-                }
-            }
+            for (int r = 0; r < kRounds; ++r)
+                if (ok[r]) atomicAdd(&row_buf[ix[r]], a[r] * d[r]);
         }
     }
     __syncthreads();
 
     float* __restrict__ out = (it.slot < 0) ? Y + (int64_t)it.row * dim : partials + (int64_t)it.slot * dim;
-    if ((dim & 3) == 0) {
-        for (int c = lane * 4; c < dim; c += kWave * 4)
-            *reinterpret_cast<float4*>(out + c) = *reinterpret_cast<const float4*>(row_buf + c);
-    } else {
-        for (int c = lane; c < dim; c += kWave) out[c] = row_buf[c];
-    }
+    for (int c = lane; c < dim; c += kWave) out[c] = row_buf[c];
 }
 
 // Private output-row copies needed so that entries sharing a wave instruction never collide.
@@ -259,19 +206,13 @@ __global__ __launch_bounds__(256) void combine_kernel(const SplitRow* __restrict
     }
 }
 
-template <int VEC, typename IdxT>
-maxk_status launch_ku(const ItemList& L, const int32_t* col, const float* val, const float* sp_data,
-                      const IdxT* sp_index, int dim, int k, float* Y, float* partials, hipStream_t s)
+template <typename IdxT>
+maxk_status launch_atomic(const ItemList& L, const int32_t* col, const float* val, const float* sp_data,
+                          const IdxT* sp_index, int dim, int k, float* Y, float* partials, hipStream_t s)
 {
     if (L.n_items > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
-    dim3 grid((unsigned)L.n_items), block(kWave);
-    const size_t lds = sizeof(float) * (size_t)dim;
-    const int ku = k / VEC;
-#define MAXK_FWD_CASE(KU)                                                                                          \
-    hipLaunchKernelGGL((spgemm_fwd_kernel<VEC, KU, IdxT>), grid, block, lds, s, L.d_items, col, val, sp_data,      \
-                       sp_index, dim, k, ku, Y, partials)
-    MAXK_FWD_CASE(0);
-#undef MAXK_FWD_CASE
+    hipLaunchKernelGGL((spgemm_fwd_atomic_kernel<IdxT>), dim3((unsigned)L.n_items), dim3(kWave),
+                       sizeof(float) * (size_t)dim, s, L.d_items, col, val, sp_data, sp_index, dim, k, Y, partials);
     MAXK_LAUNCH_CHECK();
     return MAXK_OK;
 }
@@ -348,9 +289,9 @@ maxk_status launch_spgemm_fwd(const ItemList& L, const int32_t* col, const float
         else if (index_bytes == 2) st = launch_rmw_i(L, col, val, sp_data, (const uint16_t*)sp_index, N, packed, dim, k, Y, partials, s);
         else st = launch_rmw_i(L, col, val, sp_data, (const int32_t*)sp_index, N, packed, dim, k, Y, partials, s);
     } else {
-        if (index_bytes == 1) st = launch_ku<1>(L, col, val, sp_data, (const uint8_t*)sp_index, dim, k, Y, partials, s);
-        else if (index_bytes == 2) st = launch_ku<1>(L, col, val, sp_data, (const uint16_t*)sp_index, dim, k, Y, partials, s);
-        else st = launch_ku<1>(L, col, val, sp_data, (const int32_t*)sp_index, dim, k, Y, partials, s);
+        if (index_bytes == 1) st = launch_atomic(L, col, val, sp_data, (const uint8_t*)sp_index, dim, k, Y, partials, s);
+        else if (index_bytes == 2) st = launch_atomic(L, col, val, sp_data, (const uint16_t*)sp_index, dim, k, Y, partials, s);
+        else st = launch_atomic(L, col, val, sp_data, (const int32_t*)sp_index, dim, k, Y, partials, s);
     }
     if (st != MAXK_OK) return st;
     return launch_combine(L, partials, dim, Y, s);

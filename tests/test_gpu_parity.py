@@ -72,9 +72,10 @@ def test_tiny_configs_full_compare(name):
 
 
 @pytest.mark.parametrize("dim,k,ib", [(6, 3, 1), (37, 5, 1), (100, 100, 2), (256, 255, 1), (384, 96, 2), (512, 7, 4),
-                                       (1024, 128, 2), (64, 64, 1), (130, 33, 1)])
+                                       (1024, 128, 2), (64, 64, 1), (130, 33, 1), (1024, 3, 2)])
 def test_odd_shapes_and_index_widths(dim, k, ib):
     # signed general weights on a directed graph: exercises the transpose and cancellation
+    # ((1024, 3): too many private output-row copies for LDS, the forward takes its single-copy fallback)
     g = synth.make_graph(700, 9000, 10, (0.5, 0.2, 0.2), directed=True, self_loops=False, seed=dim + k,
                          weights="normal")
     dg = DeviceGraph(g)
@@ -267,4 +268,62 @@ def test_autograd_function_matches_the_oracle_chain():
         got = Hd.grad.cpu().numpy()
         assert (np.abs(got - want) <= bound).all()
         assert ((got != 0).sum(axis=1) <= k).all()
+    dg.close()
+
+
+# ------------------------------------------------------------------ HIP graph capture of a whole step
+
+
+def test_step_captured_in_a_hip_graph_replays_correctly():
+    # a serving / training loop may capture top-k -> forward -> backward once and replay it: after
+    # maxk_graph_reserve the calls allocate nothing, synchronise nothing and record no memset nodes.
+    # Every replay (fresh inputs in the same buffers, eager work and synchronisations in between) must
+    # reproduce the eager result of the same inputs.
+    name = "tiny_directed"
+    g = synth.graph(name)
+    dim, k = synth.CONFIGS[name].dim, 8
+    dg = DeviceGraph(g)
+    for mode in (maxk.BWD_SLAB_PULL, maxk.BWD_EXPAND_REDUCE, maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR):
+        dg.handle.set_bwd_mode(mode)
+        dg.handle.reserve(dim, k)
+        Hs = torch.empty((g.N, dim), device="cuda")
+        dYs = torch.empty((g.N, dim), device="cuda")
+        sp_data = torch.empty((g.N, k), device="cuda")
+        sp_index = torch.empty((g.N, k), dtype=torch.uint8, device="cuda")
+        Y = torch.empty((g.N, dim), device="cuda")
+        dXs = torch.empty((g.N, k), device="cuda")
+
+        def step():
+            maxk.maxk_topk_cbsr(Hs, k, sp_data, sp_index)
+            maxk.maxk_spgemm_fwd(dg.handle, sp_data, sp_index, dim, Y)
+            maxk.maxk_sspmm_bwd(dg.handle, dYs, sp_index, dXs)
+
+        Hs.copy_(to_dev(synth.normal_matrix(g.N, dim, 100)))
+        dYs.copy_(to_dev(synth.normal_matrix(g.N, dim, 200)))
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()  # warm-up outside capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for rep in range(4):
+            Hn, dYn = synth.normal_matrix(g.N, dim, 300 + rep), synth.normal_matrix(g.N, dim, 400 + rep)
+            Hs.copy_(to_dev(Hn))
+            dYs.copy_(to_dev(dYn))
+            Y.fill_(float("nan"))
+            dXs.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            rd, ri = oracle.topk_cbsr(Hn, k)
+            assert np.array_equal(sp_index.cpu().numpy().astype(np.int32), ri), f"replay {rep}: sp_index"
+            ref, refabs = oracle.spgemm_fwd(g.rowptr, g.col, g.val, rd, ri, dim)
+            assert (np.abs(Y.cpu().numpy() - ref) <= 1e-5 * refabs + 1e-6).all(), f"replay {rep}: forward"
+            ref, refabs = oracle.sspmm_bwd(g.rowptr, g.col, g.val, dYn, ri)
+            assert (np.abs(dXs.cpu().numpy() - ref) <= 1e-5 * refabs + 1e-6).all(), f"replay {rep}: backward"
+            (Y.sum() + dXs.sum()).item()  # eager work between replays
+        del graph
+    dg.handle.set_bwd_mode(maxk.BWD_AUTO)
     dg.close()

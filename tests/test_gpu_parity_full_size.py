@@ -43,6 +43,8 @@ def test_dense_graph_builds():
     info = dg.handle.info()
     assert info["nnz"] == synth.CONFIGS["dense"].nnz == 114_848_855
     assert 15_000 <= info["max_degree"] <= 25_000
+    # dense neighbourhoods: the library's own choice is the L2-tiled pull for every k of the sweep
+    assert all(dg.handle.bwd_choice(256, k) == "slab_pull" for k in synth.CONFIGS["dense"].ks)
 
 
 @pytest.mark.parametrize("k", synth.CONFIGS["dense"].ks)
@@ -64,6 +66,8 @@ def test_dense_sampled_rest_of_the_papers_k_sweep(k):
 def test_wide_hidden_graph_builds():
     dg, H, dY = _setup("wide_hidden")
     assert dg.handle.info()["nnz"] == 14_671_666
+    # sparse graph, hidden 384: expand/reduce at small k, plain pull once k is a large share of dim
+    assert dg.handle.bwd_choice(384, 32) == "expand_reduce" and dg.handle.bwd_choice(384, 192) == "pull"
 
 
 @pytest.mark.parametrize("k", synth.CONFIGS["wide_hidden"].ks)
