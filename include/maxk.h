@@ -151,6 +151,11 @@ MAXK_API const char* maxk_status_string(maxk_status s);
 /* hipError_t (as int) of the last HIP failure seen by this thread, 0 if none. */
 MAXK_API int32_t maxk_last_hip_error(void);
 
+/* Host-side introspection for tests: the number of private output-row copies the forward kernel keeps in
+ * LDS for MaxK k (entries that share one 64-lane instruction must map to different copies), or a negative
+ * maxk_status for k < 1. */
+MAXK_API int32_t maxk_fwd_private_copies(int32_t k);
+
 /* Library version, MAJOR*10000 + MINOR*100 + PATCH. */
 MAXK_API int32_t maxk_version(void);
 

@@ -16,7 +16,7 @@ EXPORTS = (
     "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode", "maxk_graph_bwd_choice",
     "maxk_graph_info",
     "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_sspmm_bwd", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
-    "maxk_last_hip_error", "maxk_version",
+    "maxk_last_hip_error", "maxk_version", "maxk_fwd_private_copies",
 )
 
 
@@ -57,6 +57,8 @@ def load_library() -> ctypes.CDLL:
         getattr(lib, name).restype = i32
     lib.maxk_status_string.argtypes = [i32]
     lib.maxk_status_string.restype = ctypes.c_char_p
+    lib.maxk_fwd_private_copies.argtypes = [i32]
+    lib.maxk_fwd_private_copies.restype = i32
     lib.maxk_last_hip_error.argtypes = []
     lib.maxk_version.argtypes = []
     _LIB = lib

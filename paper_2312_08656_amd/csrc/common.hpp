@@ -92,6 +92,7 @@ maxk_status launch_spgemm_fwd(const ItemList& items, const int32_t* col, const f
                               const void* sp_index, int index_bytes, int64_t N, char* packed, int dim, int k,
                               float* Y, float* partials, hipStream_t s);
 int fwd_packed_record_bytes(int k, int index_bytes);
+int fwd_private_copies(int k);  // output-row copies the forward kernel keeps for MaxK k
 
 maxk_status launch_spmm(const ItemList& items, const int32_t* col, const float* val, const float* H, int dim,
                         float* Y, float* partials, hipStream_t s);

@@ -730,7 +730,9 @@ MAXK_API const char* maxk_status_string(maxk_status s)
     }
 }
 
-MAXK_API int32_t maxk_last_hip_error(void) { return g_last_hip_error; }
+MAXK_API int32_t maxk_fwd_private_copies(int32_t k) { return k < 1 ? MAXK_INVALID_ARGUMENT : fwd_private_copies(k); }
+
+int32_t maxk_last_hip_error(void) { return g_last_hip_error; }
 
 MAXK_API int32_t maxk_version(void) { return 100; }
 

@@ -128,7 +128,12 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* _
     float* __restrict__ row_buf = lds;                                         // nb copies of the output row
     int2* __restrict__ entry_buf = reinterpret_cast<int2*>(lds + ((nb * dim + 1) & ~1));  // 64 staged (col, val)
     const WorkItem it = items[blockIdx.x];
-    for (int c = lane; c < nb * dim; c += kWave) row_buf[c] = 0.f;
+    if (((nb * dim) & 3) == 0) {
+        for (int c = lane * 4; c < nb * dim; c += kWave * 4)
+            *reinterpret_cast<float4*>(row_buf + c) = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+        for (int c = lane; c < nb * dim; c += kWave) row_buf[c] = 0.f;
+    }
 
     for (int base = it.begin; base < it.end; base += kWave) {
         const int n = min(kWave, it.end - base);
@@ -276,6 +281,8 @@ maxk_status launch_combine(const ItemList& L, const float* partials, int width, 
 }
 
 int fwd_packed_record_bytes(int k, int index_bytes) { return (k * (4 + index_bytes) + 3) & ~3; }
+
+int fwd_private_copies(int k) { return private_copies(k); }
 
 maxk_status launch_spgemm_fwd(const ItemList& L, const int32_t* col, const float* val, const float* sp_data,
                               const void* sp_index, int index_bytes, int64_t N, char* packed, int dim, int k,

@@ -71,3 +71,19 @@ def test_binding_refuses_cpu_tensors():
     H = torch.zeros(4, 8)
     with pytest.raises(maxk.MaxKError):
         maxk.maxk_topk_cbsr(H, 2, torch.zeros(4, 2), torch.zeros(4, 2, dtype=torch.uint8))
+
+
+def test_forward_private_copies_never_collide(lib):
+    # The forward kernel walks flat units u = entry * k + position, 64 per wave instruction (aligned to
+    # multiples of 64 within a batch of 64 entries), and lets entry e accumulate into copy e % NB without
+    # atomics.  That is only safe if the entries sharing one instruction always map to distinct copies.
+    for k in list(range(1, 200)) + [255, 256, 257, 384, 512, 1000, 1024]:
+        nb = lib.maxk_fwd_private_copies(k)
+        assert nb >= 1
+        for u0 in range(0, 64 * k, 64):
+            entries = sorted({u // k for u in range(u0, u0 + 64)})
+            copies = [e % nb for e in entries]
+            assert len(set(copies)) == len(copies), (k, nb, u0)
+    assert lib.maxk_fwd_private_copies(0) < 0
+    # and it is not wasteful for the benchmark's k values
+    assert [lib.maxk_fwd_private_copies(k) for k in (8, 16, 32, 64, 96, 128, 192)] == [8, 4, 2, 1, 2, 1, 1]
