@@ -524,7 +524,7 @@ MAXK_API maxk_status maxk_graph_create(maxk_graph** out, int64_t N, int64_t nnz,
     g->d_rowptr = d_rowptr;
     g->d_col = d_colidx;
     g->d_val = d_val;
-    g->chunk = env_int("MAXK_CHUNK", 1024, 64, 1 << 20);
+    g->chunk = env_int("MAXK_CHUNK", 2048, 64, 1 << 20);  // measured plateau: 2048 and up
     (void)hipGetDevice(&g->device);
 
     maxk_status st = MAXK_OK;

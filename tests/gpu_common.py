@@ -68,7 +68,7 @@ def sample_rows(g, n_random, seed, include_longest=8):
     deg = np.diff(g.rowptr)
     rng = np.random.default_rng(seed)
     picks = [np.argsort(deg)[-include_longest:], np.argsort(deg)[:4], rng.integers(0, g.N, n_random)]
-    for target in (1023, 1024, 1025, 2048, 2049, 64, 65):
+    for target in (1023, 1024, 1025, 2047, 2048, 2049, 4096, 4097, 64, 65):
         near = np.nonzero(deg == target)[0][:2]
         picks.append(near)
     return np.unique(np.concatenate(picks)).astype(np.int64)
