@@ -389,7 +389,6 @@ __device__ __forceinline__ float load_sampled(const float* __restrict__ dY, int3
 // so that one gather instruction covers k/VEC CONSECUTIVE (ascending-column) positions of each visit
 // and every cache line of a dY row is requested by one instruction only;
 // LPD lanes per destination (power of two >= min(k / VEC, 64)); 64 / LPD visits per wave step.
-// The visit header of the next step is fetched while the current one is processed.
 // Visits longer than kSlabLongVisit entries are skipped by the lane groups and worked on by whole
 // wavefronts instead (the first n_long_blocks workgroups): the 64 / LPD groups take every G-th entry
 // and their sums are added across the wave, so a hub destination does not become the launch's tail.
@@ -458,67 +457,78 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
         }
         return;
     }
+    // The kernel is bound by L1 tag look-ups (rocprof: ~1 per clock per CU), and a load whose lanes all read
+    // one address still costs one look-up per 4 lanes.  So everything that is the same for the lanes of a
+    // visit (header, sources, values) is fetched by as few lanes as possible -- lane u of the group fetches
+    // entry u -- and handed round with lane shuffles, which do not go through the L1.
     const int64_t first = (int64_t)(blockIdx.x - n_long_blocks) * G;
     const int64_t stride = (int64_t)(gridDim.x - n_long_blocks) * G;
-    int64_t v = v_begin + first + g;
-    bool have = v < v_end;
-    int64_t j = have ? visit_node[v] : 0;
-    int b = have ? visit_begin[v] : 0, e = have ? visit_begin[v + 1] : 0;
-    // all lanes of a wave run the same number of steps (uniform loop), idle groups just skip the work
-    for (int64_t v0 = v_begin + first; v0 < v_end; v0 += stride) {
-        const int64_t vn = v + stride;
-        const bool have_n = vn < v_end;
-        const int64_t jn = have_n ? visit_node[vn] : 0;
-        const int bn = have_n ? visit_begin[vn] : 0, en = have_n ? visit_begin[vn + 1] : 0;
-        if (have && e - b <= kSlabLongVisit) {
-            for (int q = q0; q < kq; q += LPD) {  // one pass unless k / VEC > 64
-                const int64_t o = j * k + q;  // lane's positions: o + c * kq
-                int32_t my[VEC];
-                float acc[VEC];
+    const int gbase = g * LPD;  // first lane of this lane group
+    for (int64_t v0 = v_begin + first; v0 < v_end; v0 += stride) {  // uniform; one step when the grid covers all visits
+        const int64_t v = v0 + g;
+        const bool have = v < v_end;
+        int b, e;
+        int64_t j;
+        if constexpr (LPD >= 2) {
+            int hdr = 0, nd = 0;
+            if (have && q0 < 2) hdr = visit_begin[v + q0];
+            if (have && q0 == 0) nd = visit_node[v];
+            b = __shfl(hdr, gbase);
+            e = __shfl(hdr, gbase + 1);
+            j = __shfl(nd, gbase);
+        } else {
+            b = have ? visit_begin[v] : 0;
+            e = have ? visit_begin[v + 1] : 0;
+            j = have ? visit_node[v] : 0;
+        }
+        const int cnt = e - b;
+        const bool work = have && cnt <= kSlabLongVisit;
+        for (int qb = 0; qb < kq; qb += LPD) {  // one pass unless k / VEC > 64
+            const int q = qb + q0;
+            const bool active = work && q < kq;
+            const int64_t o = j * k + (active ? q : 0);  // lane's positions: o + c * kq
+            int32_t my[VEC];
+            float acc[VEC];
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) {
-                    my[c] = (int32_t)sp_index[o + c * kq];
-                    acc[c] = dXs[o + c * kq];
-                }
-                int p = b;
-                for (; p + 4 <= e; p += 4) {
+            for (int c = 0; c < VEC; ++c) {
+                my[c] = active ? (int32_t)sp_index[o + c * kq] : 0;
+                acc[c] = active ? dXs[o + c * kq] : 0.f;
+            }
+            for (int p0 = 0; p0 < kSlabLongVisit; p0 += LPD) {
+                if (!__any(work && p0 < cnt)) break;
+                const bool mine = work && p0 + q0 < cnt;
+                const int32_t src_m = mine ? slab_src[b + p0 + q0] : 0;
+                const float val_m = mine ? slab_val[b + p0 + q0] : 0.f;
+                const int nb = work ? min(LPD, cnt - p0) : 0;  // entries of this batch for this group
+                for (int u0 = 0; u0 < LPD; u0 += 4) {
+                    if (!__any(u0 < nb)) break;
                     float gv[4][VEC], a[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int32_t row = slab_src[p + u];
-                        a[u] = slab_val[p + u];
-#pragma unroll
-                        for (int c = 0; c < VEC; ++c) gv[u][c] = load_sampled<OFF32>(dY, row, dim, my[c]);
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-#pragma unroll
-                        for (int c = 0; c < VEC; ++c) acc[c] += a[u] * gv[u][c];
-                }
-                if (p < e) {  // 1..3 left: fetched together, out-of-range ones contribute zero
-                    float gv[3][VEC], a[3];
-#pragma unroll
-                    for (int u = 0; u < 3; ++u) {
-                        const bool ok = p + u < e;
-                        const int pc = ok ? p + u : b;
-                        const int32_t row = slab_src[pc];
-                        a[u] = ok ? slab_val[pc] : 0.f;
+                    for (int uu = 0; uu < 4; ++uu) {
+                        const int u = u0 + uu;
+                        const int from = gbase + (u < LPD ? u : 0);
+                        const int32_t row = __shfl(src_m, from);
+                        const float av = __shfl(val_m, from);
+                        const bool ok = active && u < nb;
+                        a[uu] = ok ? av : 0.f;
 #pragma unroll
                         for (int c = 0; c < VEC; ++c) {
-                            const float x = load_sampled<OFF32>(dY, row, dim, my[c]);
-                            gv[u][c] = ok ? x : 0.f;
+                            float x = 0.f;
+                            if (ok) x = load_sampled<OFF32>(dY, row, dim, my[c]);
+                            gv[uu][c] = x;
                         }
                     }
 #pragma unroll
-                    for (int u = 0; u < 3; ++u)
+                    for (int uu = 0; uu < 4; ++uu)
 #pragma unroll
-                        for (int c = 0; c < VEC; ++c) acc[c] += a[u] * gv[u][c];
+                        for (int c = 0; c < VEC; ++c) acc[c] += a[uu] * gv[uu][c];
                 }
+            }
+            if (active) {
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) dXs[o + c * kq] = acc[c];
             }
         }
-        v = vn; have = have_n; j = jn; b = bn; e = en;
     }
 }
 
