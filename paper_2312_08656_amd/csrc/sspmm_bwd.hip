@@ -573,8 +573,12 @@ maxk_status launch_slab_i(const SlabSet& S, const float* dY, const IdxT* sp_inde
                           float* dXs, hipStream_t s)
 {
     const bool off32 = N * (int64_t)dim * 4 <= 0xFFFFFFFFll;
-    // positions per lane: 2 up to k = 32 (16 lanes and 4 visits per wave step at k = 32), 4 above (measured)
-    if (k % 2 == 0 && k <= 32)
+    // positions per lane, measured on the dense workload (ms at k = 8 / 16 / 32 / 64 / 128):
+    //   1: 3.69 / 4.71 / 5.79 / 8.32 / 13.8     2: 3.83 / 4.83 / 5.57 / 6.75 / 14.5     4: 4.47 / 5.38 / 6.21 / 6.84 / 9.63
+    if (k <= 16)
+        return off32 ? launch_slab_t<1, true>(S, dY, sp_index, dim, k, dXs, s)
+                     : launch_slab_t<1, false>(S, dY, sp_index, dim, k, dXs, s);
+    if (k % 2 == 0 && k <= 64)
         return off32 ? launch_slab_t<2, true>(S, dY, sp_index, dim, k, dXs, s)
                      : launch_slab_t<2, false>(S, dY, sp_index, dim, k, dXs, s);
     if (k % 4 == 0)
