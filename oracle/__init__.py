@@ -13,6 +13,8 @@ Functions take and return NumPy arrays:
     sspmm_bwd(rowptr, col, val, dY, sp_index, nodes=None)           -> D f64, Dabs f64
     spmm(rowptr, col, val, H, rows=None)                            -> Y f64, Yabs f64
     cbsr_scatter(dXs, sp_index, dim)                                -> dH f32 [N,dim]
+    narrow(x, value_type)  fp32 -> uint16 patterns ("bf16" or "f16", round to nearest even)
+    widen(h, value_type)   uint16 patterns -> the fp32 values they stand for
 
 ``rows`` / ``nodes`` restrict the outputs to a sample (full-size parity checks
 compute sampled outputs one by one).  The ``*abs`` arrays hold, per output
@@ -61,6 +63,10 @@ def _load():
     lib.oracle_sspmm_bwd.restype = ctypes.c_int
     lib.oracle_cbsr_scatter.argtypes = [vp, vp, i64, i32, i32, vp]
     lib.oracle_cbsr_scatter.restype = ctypes.c_int
+    lib.oracle_narrow.argtypes = [vp, i64, i32, vp]
+    lib.oracle_narrow.restype = ctypes.c_int
+    lib.oracle_widen.argtypes = [vp, i64, i32, vp]
+    lib.oracle_widen.restype = ctypes.c_int
     lib.oracle_num_threads.argtypes = []
     lib.oracle_num_threads.restype = i32
     _lib = lib
@@ -173,3 +179,24 @@ def sspmm_bwd(rowptr, col, val, dY, sp_index, nodes=None, src_range=None):
     if rc != 0:
         raise ValueError("oracle_sspmm_bwd: bad arguments")
     return D, Dabs
+
+
+_VALUE_TYPES = {"bf16": 1, "f16": 2}
+
+
+def narrow(x, value_type: str) -> np.ndarray:
+    """CBSR values in 2 bytes: the uint16 bit patterns of x rounded to nearest even ("bf16" or "f16")."""
+    x = _c(x, np.float32)
+    out = np.empty(x.shape, np.uint16)
+    if _load().oracle_narrow(_p(x), x.size, _VALUE_TYPES[value_type], _p(out)) != 0:
+        raise ValueError("oracle_narrow: NaN in the input or bad type")
+    return out
+
+
+def widen(h, value_type: str) -> np.ndarray:
+    """The fp32 values that uint16 patterns of the given 16-bit format stand for (exact)."""
+    h = _c(h, np.uint16)
+    out = np.empty(h.shape, np.float32)
+    if _load().oracle_widen(_p(h), h.size, _VALUE_TYPES[value_type], _p(out)) != 0:
+        raise ValueError("oracle_widen: bad type")
+    return out

@@ -12,6 +12,8 @@
  *   oracle_sspmm_bwd   dXs = (A^T * dX_l) at sp_index        (Eq. 2 right, Eq. 3; Alg. 2 with destination row j)
  *   oracle_spmm        Y = A * H, dense features             (the SpMM the paper compares against, Sec. 5.2)
  *   oracle_cbsr_scatter dH from dXs: MaxK's backward          (Sec. 3.1 definition, part (ii))
+ *   oracle_narrow / oracle_widen   fp32 <-> 16-bit CBSR values (bf16, fp16), round to nearest even:
+ *                      the sp_data term of the forward traffic model, Sec. 4.3, stored in 2 bytes
  *
  * Readings of points the paper leaves open (each restated where it is used):
  *   - top-k is by signed value, exactly k survive, ties at the k-th value go
@@ -26,7 +28,9 @@
  *
  * Pins (tests/test_oracle_*.py): dense brute force on tiny graphs, k = dim
  * reduces to SpMM (scipy), identity adjacency, the adjoint identity on a
- * non-symmetric matrix, NumPy stable argsort, hand-worked goldens.
+ * non-symmetric matrix, NumPy stable argsort, hand-worked goldens; the 16-bit
+ * conversions against NumPy's float16 and PyTorch's bfloat16 casts, hand-worked
+ * halfway cases, and the round trip over all 65536 bit patterns.
  * Nothing here is "parity unpinned".
  *
  * Plain C + OpenMP over independent outputs.
@@ -215,4 +219,87 @@ int32_t oracle_num_threads(void)
 #else
     return 1;
 #endif
+}
+
+/* ------------------------------------------------- 16-bit CBSR values */
+
+/*
+ * Narrow CBSR values (the sp_data array of Sec. 3.2, whose bytes per entry enter the forward
+ * traffic model of Sec. 4.3).  type 1 = bfloat16 (1 sign, 8 exponent, 7 fraction bits),
+ * type 2 = IEEE binary16 (1, 5, 10; subnormals kept).  Rounding: to nearest, halfway cases to
+ * the even neighbour; magnitudes beyond the largest finite value round to infinity as IEEE
+ * prescribes.  NaN is outside the contract (returns -1).
+ */
+static int narrow_bf16(float x, uint16_t *out)
+{
+    uint32_t b;
+    memcpy(&b, &x, 4);
+    if (x != x) return -1;
+    /* For one sign, fp32 bit patterns grow with magnitude, and bf16 is fp32 with the low 16 bits cut:
+     * the two bf16 neighbours of x are the pattern with those bits cleared and the next one up. */
+    uint32_t below = b >> 16, rest = b & 0xFFFFu;
+    uint32_t above = below + 1u;  /* carries into the exponent (up to infinity) exactly as the value grows */
+    if (rest > 0x8000u) *out = (uint16_t)above;
+    else if (rest < 0x8000u) *out = (uint16_t)below;
+    else *out = (uint16_t)((below & 1u) ? above : below);  /* halfway: the neighbour with an even last bit */
+    return 0;
+}
+
+static int narrow_f16(float x, uint16_t *out)
+{
+    if (x != x) return -1;
+    const uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    double a = fabs((double)x);
+    if (isinf(a)) { *out = sign | 0x7C00u; return 0; }
+    /* spacing of binary16 values around a: 2^(e-10) for a in [2^e, 2^(e+1)), e >= -14; 2^-24 below 2^-14 */
+    int e;
+    (void)frexp(a, &e);        /* a = m * 2^e, m in [0.5, 1)  ->  a in [2^(e-1), 2^e) */
+    e -= 1;
+    if (a == 0.0 || e < -14) e = -14;
+    const double quantum = ldexp(1.0, e - 10);
+    const double q = nearbyint(a / quantum);   /* default rounding mode: nearest, ties to even; a/quantum is exact */
+    const double r = q * quantum;              /* the rounded magnitude, exact */
+    if (r >= 65536.0) { *out = sign | 0x7C00u; return 0; }  /* past the largest finite value 65504 */
+    if (r == 0.0) { *out = sign; return 0; }
+    if (r < ldexp(1.0, -14)) { *out = sign | (uint16_t)(r / ldexp(1.0, -24)); return 0; }  /* subnormal: fraction counts 2^-24 */
+    int er;
+    const double m = frexp(r, &er);            /* r = m * 2^er, m in [0.5, 1) */
+    const int biased = (er - 1) + 15;
+    const uint16_t frac = (uint16_t)((m * 2.0 - 1.0) * 1024.0);
+    *out = sign | (uint16_t)(biased << 10) | frac;
+    return 0;
+}
+
+int oracle_narrow(const float *x, int64_t n, int32_t type, uint16_t *out)
+{
+    if (type != 1 && type != 2) return -1;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t i = 0; i < n; ++i) bad |= (type == 1 ? narrow_bf16(x[i], &out[i]) : narrow_f16(x[i], &out[i])) != 0;
+    return bad ? -1 : 0;
+}
+
+/* The value a 16-bit pattern stands for, as fp32 (exact: both formats are subsets of fp32). */
+int oracle_widen(const uint16_t *h, int64_t n, int32_t type, float *out)
+{
+    if (type != 1 && type != 2) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const uint16_t b = h[i];
+        const int neg = b >> 15;
+        double v;
+        if (type == 1) {
+            const int ex = (b >> 7) & 0xFF, fr = b & 0x7F;
+            if (ex == 0xFF) v = fr ? NAN : INFINITY;
+            else if (ex == 0) v = ldexp((double)fr, -126 - 7);
+            else v = ldexp(1.0 + fr / 128.0, ex - 127);
+        } else {
+            const int ex = (b >> 10) & 0x1F, fr = b & 0x3FF;
+            if (ex == 0x1F) v = fr ? NAN : INFINITY;
+            else if (ex == 0) v = ldexp((double)fr, -24);
+            else v = ldexp(1.0 + fr / 1024.0, ex - 15);
+        }
+        out[i] = (float)(neg ? -v : v);
+    }
+    return 0;
 }
