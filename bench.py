@@ -39,11 +39,12 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def algorithmic_bytes(N: int, nnz: int, dim: int, k: int, index_bytes: int = 1) -> dict:
+def algorithmic_bytes(N: int, nnz: int, dim: int, k: int, index_bytes: int = 1, value_bytes: int = 4) -> dict:
     """Bytes each operator must move, from the paper's traffic model (Sec. 4.3) plus the
     adjacency and the compulsory output, which that section leaves out.
 
     fwd  : CSR (rowptr + col + val) + one CBSR row (k values + k indices) per stored entry + Y
+           (value_bytes = 2 for the 16-bit value formats of the *_narrow entry points)
     bwd  : CSR + 4k useful sampled bytes of dY per stored entry + sp_index and dXs once
            (design-independent count; the paper's push design moves 4*N*dim + (4+ib)*k*nnz
            reads and 4*k*nnz writes, reported separately)
@@ -53,11 +54,11 @@ def algorithmic_bytes(N: int, nnz: int, dim: int, k: int, index_bytes: int = 1) 
     ib = index_bytes
     csr = 4 * (N + 1) + 8 * nnz
     return {
-        "fwd_cbsr_reads": (4 + ib) * k * nnz,
+        "fwd_cbsr_reads": (value_bytes + ib) * k * nnz,
         "spmm_feature_reads": 4 * dim * nnz,
         "bwd_paper_reads": 4 * N * dim + (4 + ib) * k * nnz,
         "bwd_paper_writes": 4 * k * nnz,
-        "fwd": csr + (4 + ib) * k * nnz + 4 * N * dim,
+        "fwd": csr + (value_bytes + ib) * k * nnz + 4 * N * dim,
         "bwd": csr + 4 * k * nnz + N * k * (ib + 4),
         "topk": 4 * N * dim + N * k * (4 + ib),
         "spmm": csr + 4 * nnz * dim + 4 * N * dim,
@@ -206,6 +207,15 @@ def main() -> int:
             row = {"k": k, "topk_ms": round(tk, 4), "fwd_ms": round(tf, 4), "fwd_ms_median": round(tf_med, 4),
                    "fwd_edges_k_per_s": nnz * k / (tf * 1e-3), "fwd_hbm_frac": round(b["fwd"] / (tf * 1e-3) / 8e12, 4),
                    "fwd_speedup_vs_spmm": round(spmm_ms / tf, 2)}
+            # the same forward pass with the CBSR values stored in 2 bytes (fp32 accumulation; not the headline)
+            b16 = algorithmic_bytes(N, nnz, dim, k, ib, value_bytes=2)
+            for name, dt in (("bf16", torch.bfloat16), ("f16", torch.float16)):
+                sd16 = torch.empty((N, k), dtype=dt, device="cuda")
+                maxk.maxk_topk_cbsr_narrow(Hd, k, sd16, si)
+                t16, _ = timeit(lambda: maxk.maxk_spgemm_fwd_narrow(gr, sd16, si, dim, Y), args.sweep_reps)
+                row.update({f"fwd_{name}_values_ms": round(t16, 4),
+                            f"fwd_{name}_values_hbm_frac": round(b16["fwd"] / (t16 * 1e-3) / 8e12, 4)})
+                del sd16
             for mode, tag in ((maxk.BWD_PUSH_CSR, "bwd_push"), (maxk.BWD_PULL_CSC, "bwd_pull"),
                               (maxk.BWD_EXPAND_REDUCE, "bwd_expand_reduce"), (maxk.BWD_SLAB_PULL, "bwd_slab_pull")):
                 gr.set_bwd_mode(mode)

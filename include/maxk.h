@@ -64,6 +64,13 @@ enum {
                                   swept slab by slab, one launch per slab; deterministic, no atomics */
 };
 
+/* Storage format of the CBSR values for the *_narrow entry points: fp32, or a 16-bit pattern in a uint16_t. */
+enum {
+    MAXK_VALUE_F32 = 0,
+    MAXK_VALUE_BF16 = 1, /* bfloat16: the upper half of the fp32 pattern, 8 significant bits */
+    MAXK_VALUE_F16 = 2   /* IEEE binary16, 11 significant bits, subnormals kept, |x| >= 65520 becomes infinity */
+};
+
 typedef struct maxk_graph maxk_graph;
 
 /*
@@ -121,6 +128,22 @@ MAXK_API maxk_status maxk_topk_cbsr(const float* d_H, int64_t N, int32_t dim, in
  */
 MAXK_API maxk_status maxk_spgemm_fwd(maxk_graph* g, const float* d_sp_data, const void* d_sp_index, int32_t index_bytes,
                             int32_t dim, int32_t k, float* d_Y, void* stream);
+
+/*
+ * The same two steps with the CBSR values stored in 2 bytes (value_type MAXK_VALUE_BF16 or _F16;
+ * MAXK_VALUE_F32 makes them the plain calls).  The forward pass reads (4+ib) bytes per stored entry and
+ * kept position (Sec. 4.3, traffic model of the SpGEMM); 16-bit values make that (2+ib).  Selection is done
+ * on the fp32 input, so d_sp_index is identical to maxk_topk_cbsr's; d_sp_data[i,t] is the fp32 value
+ * rounded to nearest (halfway cases to even), laid out [N x k] in uint16_t.  The forward kernel widens the
+ * stored values exactly and multiplies and accumulates in fp32, so Y differs from the fp32 path only
+ * through the rounding of the values: by at most 2^-8 (bf16) or 2^-11 (fp16, |x| in [6.2e-5, 65504])
+ * of the sum of |terms| per element.  The backward pass does not read the values and is unchanged.
+ */
+MAXK_API maxk_status maxk_topk_cbsr_narrow(const float* d_H, int64_t N, int32_t dim, int32_t k, void* d_sp_data,
+                                           int32_t value_type, void* d_sp_index, int32_t index_bytes, void* stream);
+MAXK_API maxk_status maxk_spgemm_fwd_narrow(maxk_graph* g, const void* d_sp_data, int32_t value_type,
+                                            const void* d_sp_index, int32_t index_bytes, int32_t dim, int32_t k,
+                                            float* d_Y, void* stream);
 
 /*
  * Backward aggregation, sampled SSpMM (Eq. 2 right; Eq. 3; Alg. 2 with the

@@ -12,6 +12,9 @@ from .binding import (  # noqa: F401
     BWD_PULL_CSC,
     BWD_PUSH_CSR,
     BWD_SLAB_PULL,
+    VALUE_BF16,
+    VALUE_F16,
+    VALUE_F32,
     MaxKError,
     MaxKGraph,
     index_dtype,
@@ -21,8 +24,10 @@ from .binding import (  # noqa: F401
     maxk_graph_create,
     maxk_graph_destroy,
     maxk_spgemm_fwd,
+    maxk_spgemm_fwd_narrow,
     maxk_sspmm_bwd,
     maxk_topk_cbsr,
+    maxk_topk_cbsr_narrow,
     spmm_baseline,
 )
 from .autograd import MaxKAggregate, maxk_aggregate  # noqa: E402,F401

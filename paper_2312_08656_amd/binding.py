@@ -11,11 +11,12 @@ _HERE = Path(__file__).resolve().parent
 _LIB: Optional[ctypes.CDLL] = None
 
 BWD_AUTO, BWD_PULL_CSC, BWD_PUSH_CSR, BWD_EXPAND_REDUCE, BWD_SLAB_PULL = 0, 1, 2, 3, 4
+VALUE_F32, VALUE_BF16, VALUE_F16 = 0, 1, 2
 
 EXPORTS = (
     "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode", "maxk_graph_bwd_choice",
     "maxk_graph_info",
-    "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_sspmm_bwd", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
+    "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_topk_cbsr_narrow", "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
     "maxk_last_hip_error", "maxk_version", "maxk_fwd_private_copies",
 )
 
@@ -47,11 +48,14 @@ def load_library() -> ctypes.CDLL:
     lib.maxk_graph_info.argtypes = [vp] + [ctypes.POINTER(i64)] * 6
     lib.maxk_topk_cbsr.argtypes = [vp, i64, i32, i32, vp, vp, i32, vp]
     lib.maxk_spgemm_fwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.maxk_topk_cbsr_narrow.argtypes = [vp, i64, i32, i32, vp, i32, vp, i32, vp]
+    lib.maxk_spgemm_fwd_narrow.argtypes = [vp, vp, i32, vp, i32, i32, i32, vp, vp]
     lib.maxk_sspmm_bwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     lib.maxk_cbsr_scatter.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp]
     lib.spmm_baseline.argtypes = [vp, vp, i32, vp, vp]
     for name in ("maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode",
-                 "maxk_graph_info", "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_sspmm_bwd", "maxk_cbsr_scatter",
+                 "maxk_graph_info", "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_topk_cbsr_narrow",
+                 "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd", "maxk_cbsr_scatter",
                  "spmm_baseline",
                  "maxk_last_hip_error", "maxk_version"):
         getattr(lib, name).restype = i32
@@ -87,6 +91,7 @@ def index_dtype(index_bytes: int):
 
 
 _INDEX_BYTES = {torch.uint8: 1, torch.uint16: 2, torch.int16: 2, torch.int32: 4}
+_VALUE_TYPE = {torch.float32: VALUE_F32, torch.bfloat16: VALUE_BF16, torch.float16: VALUE_F16}
 
 
 class MaxKGraph:
@@ -169,6 +174,35 @@ def maxk_spgemm_fwd(g: MaxKGraph, sp_data: torch.Tensor, sp_index: torch.Tensor,
     _check(load_library().maxk_spgemm_fwd(g.handle, _dev(sp_data, torch.float32, "sp_data"),
                                           _dev(sp_index, sp_index.dtype, "sp_index"), ib, dim, k,
                                           _dev(Y, torch.float32, "Y"), _stream()), "maxk_spgemm_fwd")
+
+
+def maxk_topk_cbsr_narrow(H: torch.Tensor, k: int, sp_data: torch.Tensor, sp_index: torch.Tensor) -> None:
+    """As maxk_topk_cbsr, the values stored in sp_data's own dtype (bfloat16, float16 or float32)."""
+    N, dim = H.shape
+    ib = _INDEX_BYTES[sp_index.dtype]
+    if sp_data.dtype not in _VALUE_TYPE:
+        raise MaxKError("maxk_topk_cbsr_narrow: sp_data must be float32, bfloat16 or float16")
+    if tuple(sp_data.shape) != (N, k) or tuple(sp_index.shape) != (N, k):
+        raise MaxKError("maxk_topk_cbsr_narrow: sp_data / sp_index must be [N, k]")
+    _check(load_library().maxk_topk_cbsr_narrow(_dev(H, torch.float32, "H"), N, dim, k,
+                                                _dev(sp_data, sp_data.dtype, "sp_data"), _VALUE_TYPE[sp_data.dtype],
+                                                _dev(sp_index, sp_index.dtype, "sp_index"), ib, _stream()),
+           "maxk_topk_cbsr_narrow")
+
+
+def maxk_spgemm_fwd_narrow(g: MaxKGraph, sp_data: torch.Tensor, sp_index: torch.Tensor, dim: int,
+                           Y: torch.Tensor) -> None:
+    """As maxk_spgemm_fwd with the CBSR values in sp_data's own dtype (bfloat16, float16 or float32)."""
+    N, k = sp_data.shape
+    if sp_data.dtype not in _VALUE_TYPE:
+        raise MaxKError("maxk_spgemm_fwd_narrow: sp_data must be float32, bfloat16 or float16")
+    if N != g.N or tuple(sp_index.shape) != (N, k) or tuple(Y.shape) != (N, dim):
+        raise MaxKError("maxk_spgemm_fwd_narrow: shape mismatch")
+    ib = _INDEX_BYTES[sp_index.dtype]
+    _check(load_library().maxk_spgemm_fwd_narrow(g.handle, _dev(sp_data, sp_data.dtype, "sp_data"),
+                                                 _VALUE_TYPE[sp_data.dtype], _dev(sp_index, sp_index.dtype, "sp_index"),
+                                                 ib, dim, k, _dev(Y, torch.float32, "Y"), _stream()),
+           "maxk_spgemm_fwd_narrow")
 
 
 def maxk_sspmm_bwd(g: MaxKGraph, dY: torch.Tensor, sp_index: torch.Tensor, dXs: torch.Tensor) -> None:

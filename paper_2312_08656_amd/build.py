@@ -10,7 +10,8 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libmaxk.so"
-SOURCES = ["graph.hip", "topk.hip", "spgemm_fwd.hip", "sspmm_bwd.hip", "spmm.hip"]
+SOURCES = ["graph.hip", "topk.hip", "spgemm_fwd.hip", "spgemm_fwd_f32.hip", "spgemm_fwd_bf16.hip", "spgemm_fwd_f16.hip",
+           "sspmm_bwd.hip", "spmm.hip"]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions from float code
 HIPCC_FLAGS = [

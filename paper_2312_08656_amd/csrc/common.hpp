@@ -77,21 +77,58 @@ inline maxk_status hip_fail(hipError_t e)
         if (_e != hipSuccess) return ::maxk::hip_fail(_e);   \
     } while (0)
 
+// ---- storage formats of CBSR values: MAXK_VALUE_F32 / _BF16 / _F16 (the 16-bit ones are bit patterns in uint16_t) ----
+
+template <int VT>
+struct value_store { using type = uint16_t; };
+template <>
+struct value_store<MAXK_VALUE_F32> { using type = float; };
+template <int VT>
+using value_store_t = typename value_store<VT>::type;
+
+inline int value_bytes(int value_type) { return value_type == MAXK_VALUE_F32 ? 4 : 2; }
+
+// the fp32 value a stored pattern stands for (exact)
+template <int VT>
+__device__ __forceinline__ float widen_value(value_store_t<VT> x)
+{
+    if constexpr (VT == MAXK_VALUE_F32) return x;
+    else if constexpr (VT == MAXK_VALUE_BF16) return __uint_as_float((uint32_t)x << 16);
+    else return (float)__builtin_bit_cast(_Float16, x);
+}
+
+// round to nearest, halfway cases to even; beyond the largest finite value -> infinity (NaN is outside the contract)
+template <int VT>
+__device__ __forceinline__ value_store_t<VT> narrow_value(float x)
+{
+    if constexpr (VT == MAXK_VALUE_F32) return x;
+    else if constexpr (VT == MAXK_VALUE_BF16) {
+        const uint32_t b = __float_as_uint(x);
+        // adding 0x7FFF (+1 when the kept part is odd) carries into the kept part exactly when the cut-off
+        // part is above one half, or equals one half next to an odd neighbour
+        return (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+    } else {
+        return __builtin_bit_cast(uint16_t, (_Float16)x);  // v_cvt_f16_f32, round-to-nearest-even mode, subnormals kept
+    }
+}
+
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // ---- launchers implemented in the kernel files (device pointers throughout) ----
 
-maxk_status launch_topk(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
-                        hipStream_t s);
+maxk_status launch_topk(const float* H, int64_t N, int dim, int k, void* sp_data, int value_type, void* sp_index,
+                        int index_bytes, hipStream_t s);
 
 maxk_status launch_cbsr_scatter(const float* values, const void* sp_index, int index_bytes, int64_t N, int dim, int k,
                                 float* dense, hipStream_t s);
 
-// `packed`: workspace of N * fwd_packed_record_bytes(k, index_bytes) bytes to use the packed-record path, or null
-maxk_status launch_spgemm_fwd(const ItemList& items, const int32_t* col, const float* val, const float* sp_data,
-                              const void* sp_index, int index_bytes, int64_t N, char* packed, int dim, int k,
-                              float* Y, float* partials, hipStream_t s);
-int fwd_packed_record_bytes(int k, int index_bytes);
+// `packed`: workspace of N * fwd_packed_record_bytes(k, index_bytes, value bytes) bytes to use the packed-record
+// path, or null
+maxk_status launch_spgemm_fwd(const ItemList& items, const int32_t* col, const float* val, const void* sp_data,
+                              int value_type, const void* sp_index, int index_bytes, int64_t N, char* packed, int dim,
+                              int k, float* Y, float* partials, hipStream_t s);
+int fwd_packed_index_offset(int k, int index_bytes, int val_bytes);  // where a record's indices start
+int fwd_packed_record_bytes(int k, int index_bytes, int val_bytes);
 int fwd_private_copies(int k);  // output-row copies the forward kernel keeps for MaxK k
 
 maxk_status launch_spmm(const ItemList& items, const int32_t* col, const float* val, const float* H, int dim,

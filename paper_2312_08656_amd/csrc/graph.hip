@@ -439,14 +439,14 @@ int32_t slab_rows_for(int dim)
 }
 
 // The forward kernel repacks the CBSR when a row of it is well below a cache line.
-bool fwd_uses_packed(int k, int index_bytes)
+bool fwd_uses_packed(int k, int index_bytes, int val_bytes)
 {
-    return k * (4 + index_bytes) <= env_int("MAXK_FWD_PACK_MAX", 96, 0, 1 << 20);
+    return k * (val_bytes + index_bytes) <= env_int("MAXK_FWD_PACK_MAX", 96, 0, 1 << 20);
 }
 
-maxk_status ensure_packed(maxk_graph* g, int k, int index_bytes)
+maxk_status ensure_packed(maxk_graph* g, int k, int index_bytes, int val_bytes)
 {
-    const int64_t need = g->N * (int64_t)fwd_packed_record_bytes(k, index_bytes);
+    const int64_t need = g->N * (int64_t)fwd_packed_record_bytes(k, index_bytes, val_bytes);
     if (need <= g->packed_bytes) return MAXK_OK;
     char* fresh = nullptr;
     MAXK_HIP_TRY(hipMalloc((void**)&fresh, (size_t)need));
@@ -587,12 +587,14 @@ MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k)
     if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
     maxk_status st = ensure_workspace(g, dim, k);
     if (st != MAXK_OK) return st;
-    for (int ib = 1; ib <= 4; ib *= 2) {
-        for (int kk = 1; kk <= k; ++kk) {  // the largest repacked record among k' <= k
-            if (!fwd_uses_packed(kk, ib)) break;
-            if (kk == k || !fwd_uses_packed(kk + 1, ib)) {
-                st = ensure_packed(g, kk, ib);
-                if (st != MAXK_OK) return st;
+    for (int vb = 2; vb <= 4; vb += 2) {
+        for (int ib = 1; ib <= 4; ib *= 2) {
+            for (int kk = 1; kk <= k; ++kk) {  // the largest repacked record among k' <= k
+                if (!fwd_uses_packed(kk, ib, vb)) break;
+                if (kk == k || !fwd_uses_packed(kk + 1, ib, vb)) {
+                    st = ensure_packed(g, kk, ib, vb);
+                    if (st != MAXK_OK) return st;
+                }
             }
         }
     }
@@ -628,38 +630,55 @@ MAXK_API maxk_status maxk_graph_info(const maxk_graph* g, int64_t* N, int64_t* n
     return MAXK_OK;
 }
 
-MAXK_API maxk_status maxk_topk_cbsr(const float* d_H, int64_t N, int32_t dim, int32_t k, float* d_sp_data, void* d_sp_index,
-                           int32_t index_bytes, void* stream)
+MAXK_API maxk_status maxk_topk_cbsr_narrow(const float* d_H, int64_t N, int32_t dim, int32_t k, void* d_sp_data,
+                                           int32_t value_type, void* d_sp_index, int32_t index_bytes, void* stream)
 {
     if (N < 0 || dim < 1 || k < 1 || k > dim || bad_index_bytes(index_bytes, dim)) return MAXK_INVALID_ARGUMENT;
+    if (value_type < MAXK_VALUE_F32 || value_type > MAXK_VALUE_F16) return MAXK_INVALID_ARGUMENT;
     if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
     if (N > 0x7FFFFFF0ll) return MAXK_INVALID_ARGUMENT;
     if (N == 0) return MAXK_OK;
     if (!d_H || !d_sp_data || !d_sp_index) return MAXK_INVALID_ARGUMENT;
-    if (!aligned(d_H, 4) || !aligned(d_sp_data, 4) || !aligned(d_sp_index, (size_t)index_bytes))
+    if (!aligned(d_H, 4) || !aligned(d_sp_data, (size_t)value_bytes(value_type)) ||
+        !aligned(d_sp_index, (size_t)index_bytes))
         return MAXK_INVALID_ARGUMENT;
-    return launch_topk(d_H, N, dim, k, d_sp_data, d_sp_index, index_bytes, (hipStream_t)stream);
+    return launch_topk(d_H, N, dim, k, d_sp_data, value_type, d_sp_index, index_bytes, (hipStream_t)stream);
+}
+
+MAXK_API maxk_status maxk_topk_cbsr(const float* d_H, int64_t N, int32_t dim, int32_t k, float* d_sp_data, void* d_sp_index,
+                           int32_t index_bytes, void* stream)
+{
+    return maxk_topk_cbsr_narrow(d_H, N, dim, k, d_sp_data, MAXK_VALUE_F32, d_sp_index, index_bytes, stream);
+}
+
+MAXK_API maxk_status maxk_spgemm_fwd_narrow(maxk_graph* g, const void* d_sp_data, int32_t value_type,
+                                            const void* d_sp_index, int32_t index_bytes, int32_t dim, int32_t k,
+                                            float* d_Y, void* stream)
+{
+    if (!g || dim < 1 || k < 1 || k > dim || bad_index_bytes(index_bytes, dim)) return MAXK_INVALID_ARGUMENT;
+    if (value_type < MAXK_VALUE_F32 || value_type > MAXK_VALUE_F16) return MAXK_INVALID_ARGUMENT;
+    if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
+    if (g->N == 0) return MAXK_OK;
+    if (!d_sp_data || !d_sp_index || !d_Y) return MAXK_INVALID_ARGUMENT;
+    const int vb = value_bytes(value_type);
+    if (!aligned(d_sp_data, (size_t)vb) || !aligned(d_Y, 4) || !aligned(d_sp_index, (size_t)index_bytes))
+        return MAXK_INVALID_ARGUMENT;
+    maxk_status st = ensure_workspace(g, dim, k);
+    if (st != MAXK_OK) return st;
+    char* packed = nullptr;
+    if (fwd_uses_packed(k, index_bytes, vb)) {
+        st = ensure_packed(g, k, index_bytes, vb);
+        if (st != MAXK_OK) return st;
+        packed = g->d_packed;
+    }
+    return launch_spgemm_fwd(g->csr_items, g->d_col, g->d_val, d_sp_data, value_type, d_sp_index, index_bytes, g->N, packed,
+                             dim, k, d_Y, g->d_partials, (hipStream_t)stream);
 }
 
 MAXK_API maxk_status maxk_spgemm_fwd(maxk_graph* g, const float* d_sp_data, const void* d_sp_index, int32_t index_bytes,
                             int32_t dim, int32_t k, float* d_Y, void* stream)
 {
-    if (!g || dim < 1 || k < 1 || k > dim || bad_index_bytes(index_bytes, dim)) return MAXK_INVALID_ARGUMENT;
-    if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
-    if (g->N == 0) return MAXK_OK;
-    if (!d_sp_data || !d_sp_index || !d_Y) return MAXK_INVALID_ARGUMENT;
-    if (!aligned(d_sp_data, 4) || !aligned(d_Y, 4) || !aligned(d_sp_index, (size_t)index_bytes))
-        return MAXK_INVALID_ARGUMENT;
-    maxk_status st = ensure_workspace(g, dim, k);
-    if (st != MAXK_OK) return st;
-    char* packed = nullptr;
-    if (fwd_uses_packed(k, index_bytes)) {
-        st = ensure_packed(g, k, index_bytes);
-        if (st != MAXK_OK) return st;
-        packed = g->d_packed;
-    }
-    return launch_spgemm_fwd(g->csr_items, g->d_col, g->d_val, d_sp_data, d_sp_index, index_bytes, g->N, packed, dim, k, d_Y,
-                             g->d_partials, (hipStream_t)stream);
+    return maxk_spgemm_fwd_narrow(g, d_sp_data, MAXK_VALUE_F32, d_sp_index, index_bytes, dim, k, d_Y, stream);
 }
 
 MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void* d_sp_index, int32_t index_bytes, int32_t dim,

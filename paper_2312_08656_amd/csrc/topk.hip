@@ -60,9 +60,11 @@ __device__ __forceinline__ void column_order_prefix(const bool (&flag)[E], int (
     }
 }
 
-template <int E, int V, typename IdxT>
+// VT: storage format of the values written (MAXK_VALUE_*); selection always works on the fp32 input
+template <int E, int V, int VT, typename IdxT>
 __global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict__ H, int64_t N, int dim, int k,
-                                                        float* __restrict__ sp_data, IdxT* __restrict__ sp_index)
+                                                        value_store_t<VT>* __restrict__ sp_data,
+                                                        IdxT* __restrict__ sp_index)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t row = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
@@ -132,12 +134,12 @@ __global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict_
 
     int pos[E];
     column_order_prefix<E, V>(sel, pos);
-    float* __restrict__ od = sp_data + row * (int64_t)k;
+    value_store_t<VT>* __restrict__ od = sp_data + row * (int64_t)k;
     IdxT* __restrict__ oi = sp_index + row * (int64_t)k;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         if (sel[e]) {
-            od[pos[e]] = v[e];
+            od[pos[e]] = narrow_value<VT>(v[e]);
             oi[pos[e]] = (IdxT)column_of<V>(lane, e);
         }
     }
@@ -165,21 +167,31 @@ __global__ __launch_bounds__(256) void cbsr_scatter_kernel(const float* __restri
     }
 }
 
-template <int E, int V>
-maxk_status launch_e(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
+template <int E, int V, int VT>
+maxk_status launch_v(const float* H, int64_t N, int dim, int k, void* sp_data, void* sp_index, int index_bytes,
                      hipStream_t s)
 {
     const int rows_per_block = 4;
     const int64_t blocks = (N + rows_per_block - 1) / rows_per_block;
     if (blocks > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
     dim3 grid((unsigned)blocks), block(rows_per_block * kWave);
+    auto* od = (value_store_t<VT>*)sp_data;
     switch (index_bytes) {
-        case 1: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, uint8_t>), grid, block, 0, s, H, N, dim, k, sp_data, (uint8_t*)sp_index); break;
-        case 2: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, uint16_t>), grid, block, 0, s, H, N, dim, k, sp_data, (uint16_t*)sp_index); break;
-        default: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, int32_t>), grid, block, 0, s, H, N, dim, k, sp_data, (int32_t*)sp_index); break;
+        case 1: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, VT, uint8_t>), grid, block, 0, s, H, N, dim, k, od, (uint8_t*)sp_index); break;
+        case 2: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, VT, uint16_t>), grid, block, 0, s, H, N, dim, k, od, (uint16_t*)sp_index); break;
+        default: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, VT, int32_t>), grid, block, 0, s, H, N, dim, k, od, (int32_t*)sp_index); break;
     }
     MAXK_LAUNCH_CHECK();
     return MAXK_OK;
+}
+
+template <int E, int V>
+maxk_status launch_e(const float* H, int64_t N, int dim, int k, void* sp_data, int value_type, void* sp_index,
+                     int index_bytes, hipStream_t s)
+{
+    if (value_type == MAXK_VALUE_BF16) return launch_v<E, V, MAXK_VALUE_BF16>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+    if (value_type == MAXK_VALUE_F16) return launch_v<E, V, MAXK_VALUE_F16>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+    return launch_v<E, V, MAXK_VALUE_F32>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
 }
 
 }  // namespace
@@ -199,20 +211,20 @@ maxk_status launch_cbsr_scatter(const float* values, const void* sp_index, int i
     return MAXK_OK;
 }
 
-maxk_status launch_topk(const float* H, int64_t N, int dim, int k, float* sp_data, void* sp_index, int index_bytes,
-                        hipStream_t s)
+maxk_status launch_topk(const float* H, int64_t N, int dim, int k, void* sp_data, int value_type, void* sp_index,
+                        int index_bytes, hipStream_t s)
 {
     if (N == 0) return MAXK_OK;
     const bool vec = (dim % 4 == 0) && aligned(H, 16);
     if (vec) {
-        if (dim <= 256) return launch_e<4, 4>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
-        if (dim <= 512) return launch_e<8, 4>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
-        return launch_e<16, 4>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+        if (dim <= 256) return launch_e<4, 4>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+        if (dim <= 512) return launch_e<8, 4>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+        return launch_e<16, 4>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
     }
-    if (dim <= 64) return launch_e<1, 1>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
-    if (dim <= 256) return launch_e<4, 1>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
-    if (dim <= 512) return launch_e<8, 1>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
-    return launch_e<16, 1>(H, N, dim, k, sp_data, sp_index, index_bytes, s);
+    if (dim <= 64) return launch_e<1, 1>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+    if (dim <= 256) return launch_e<4, 1>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+    if (dim <= 512) return launch_e<8, 1>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+    return launch_e<16, 1>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
 }
 
 }  // namespace maxk

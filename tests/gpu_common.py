@@ -116,6 +116,43 @@ def check_spmm(dg, H, H_dev, rows=None):
     return ratio
 
 
+_NARROW = {"bf16": (torch.bfloat16, 2.0 ** -8), "f16": (torch.float16, 2.0 ** -11)}
+
+
+def check_narrow(dg, H_dev, k, index_bytes, ref_cbsr, dim, rows=None):
+    """16-bit CBSR values: top-k writes the oracle's rounding of the fp32 values bit for bit (same indices);
+    the forward pass on them meets the usual bound against the oracle run on the widened values, and stays
+    within the format's rounding error of the fp32 result."""
+    g = dg.host
+    N = g.N
+    ref32, refabs32 = oracle.spgemm_fwd(g.rowptr, g.col, g.val, ref_cbsr[0], ref_cbsr[1], dim, rows=rows)
+    worst = {}
+    for vt, (dtype, half_ulp) in _NARROW.items():
+        sp_data = torch.empty((N, k), dtype=dtype, device="cuda")
+        sp_index = torch.empty((N, k), dtype=maxk.index_dtype(index_bytes), device="cuda")
+        if N * k:
+            sp_data.fill_(float("nan"))
+        maxk.maxk_topk_cbsr_narrow(H_dev, k, sp_data, sp_index)
+        torch.cuda.synchronize()
+        assert np.array_equal(index_to_numpy(sp_index), ref_cbsr[1]), f"{vt}: sp_index differs from the oracle"
+        bits = sp_data.view(torch.int16).cpu().numpy().view(np.uint16)
+        want = oracle.narrow(ref_cbsr[0], vt)
+        assert np.array_equal(bits, want), f"{vt}: stored values differ from the oracle's rounding"
+        Y = torch.full((N, dim), float("nan"), dtype=torch.float32, device="cuda")
+        maxk.maxk_spgemm_fwd_narrow(dg.handle, sp_data, sp_index, dim, Y)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(Y).all()), f"{vt}: forward left non-finite / unwritten output"
+        got = Y.cpu().numpy() if rows is None else Y[torch.from_numpy(rows).cuda()].cpu().numpy()
+        ref, refabs = oracle.spgemm_fwd(g.rowptr, g.col, g.val, oracle.widen(want, vt), ref_cbsr[1], dim, rows=rows)
+        ok, ratio = within_bound(got, ref, refabs)
+        assert ok, f"{vt}: forward outside the bound (worst err/bound = {ratio:.3f})"
+        # against the fp32 definition: each term is off by at most half a unit in the last kept place
+        drift = np.abs(got.astype(np.float64) - ref32)
+        assert np.all(drift <= (half_ulp + 1e-5) * refabs32 + 2e-6), f"{vt}: forward drifts from fp32 by more than rounding"
+        worst[vt] = ratio
+    return worst
+
+
 def check_adjoint(Y_dev, dY_dev, sp_data_dev, dXs_dev, rel=1e-4):
     """<A X, dY> = <X, A^T dY> on the GPU outputs (holds at any size; fp64 reduction)."""
     lhs = float((Y_dev.double() * dY_dev.double()).sum())
@@ -124,7 +161,7 @@ def check_adjoint(Y_dev, dY_dev, sp_data_dev, dXs_dev, rel=1e-4):
     assert abs(lhs - rhs) <= rel * scale, f"adjoint identity violated: {lhs} vs {rhs} (scale {scale})"
 
 
-def full_pass(dg, H, dY, k, index_bytes, sampled, seed=0, n_random=1500, spmm=True):
+def full_pass(dg, H, dY, k, index_bytes, sampled, seed=0, n_random=1500, spmm=True, narrow=True):
     """top-k -> forward -> backward (both kernels) -> dense SpMM, each checked against the oracle."""
     g = dg.host
     dim = H.shape[1]
@@ -148,3 +185,6 @@ def full_pass(dg, H, dY, k, index_bytes, sampled, seed=0, n_random=1500, spmm=Tr
     if spmm:
         rs = check_spmm(dg, H, H_dev, rows)
         say(f"    dense SpMM ok, worst err/bound {rs:.3f} ({time.time() - t0:.1f}s)")
+    if narrow:
+        rn = check_narrow(dg, H_dev, k, index_bytes, ref, dim, rows)
+        say(f"    16-bit values ok, worst err/bound {rn} ({time.time() - t0:.1f}s)")

@@ -327,3 +327,48 @@ def test_step_captured_in_a_hip_graph_replays_correctly():
         del graph
     dg.handle.set_bwd_mode(maxk.BWD_AUTO)
     dg.close()
+
+
+@pytest.mark.parametrize("vt,dtype", [("bf16", "bfloat16"), ("f16", "float16")])
+def test_narrow_values_round_like_the_oracle_on_special_values(vt, dtype):
+    """Halfway cases, the fp16 subnormal range, overflow to infinity, signed zeros: with k = dim the
+    top-k call stores every value of the row, so the stored bits are the rounding of the whole input."""
+    rng = np.random.default_rng(11)
+    base = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 2049.0, 2051.0, 65504.0,
+                     65519.0, 65520.0, 1e6, -1e6, 3.3e38, -3.3e38, 2.0 ** -14, 2.0 ** -15, 2.0 ** -24, 2.0 ** -25,
+                     3 * 2.0 ** -25, 2.0 ** -26, 1e-30, -1e-30, 0.0, -0.0, 0.1, -0.1, np.inf, -np.inf], np.float32)
+    dim = 64
+    rows = [np.resize(base, dim), np.resize(-base, dim)]
+    rows += [(rng.standard_normal(dim) * np.exp2(rng.integers(-30, 18, dim))).astype(np.float32) for _ in range(200)]
+    bits = rng.integers(0, 2 ** 32, (400, dim), dtype=np.uint64).astype(np.uint32).view(np.float32)
+    bits[~np.isfinite(bits)] = 1.0
+    H = np.ascontiguousarray(np.vstack(rows + [bits]), dtype=np.float32)
+    N = H.shape[0]
+    sp_data = torch.empty((N, dim), dtype=getattr(torch, dtype), device="cuda")
+    sp_index = torch.empty((N, dim), dtype=torch.uint8, device="cuda")
+    maxk.maxk_topk_cbsr_narrow(to_dev(H), dim, sp_data, sp_index)
+    torch.cuda.synchronize()
+    assert np.array_equal(sp_index.cpu().numpy(), np.tile(np.arange(dim, dtype=np.uint8), (N, 1)))
+    got = sp_data.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, oracle.narrow(H, vt))
+
+
+def test_narrow_entry_points_with_fp32_values_are_the_plain_calls():
+    cfg = synth.CONFIGS["tiny_directed"]
+    g = synth.graph("tiny_directed")
+    dg = DeviceGraph(g)
+    H = synth.features("tiny_directed", "H")
+    k = cfg.ks[0]
+    a_d, a_i = gpu_topk(to_dev(H), k, 1)
+    b_d = torch.empty_like(a_d)
+    b_i = torch.empty_like(a_i)
+    maxk.maxk_topk_cbsr_narrow(to_dev(H), k, b_d, b_i)
+    assert torch.equal(a_d.view(torch.int32), b_d.view(torch.int32)) and torch.equal(a_i, b_i)
+    Y1 = torch.empty((g.N, cfg.dim), device="cuda")
+    Y2 = torch.empty_like(Y1)
+    maxk.maxk_spgemm_fwd(dg.handle, a_d, a_i, cfg.dim, Y1)
+    maxk.maxk_spgemm_fwd_narrow(dg.handle, b_d, b_i, cfg.dim, Y2)
+    ref, refabs = oracle.spgemm_fwd(g.rowptr, g.col, g.val, *oracle.topk_cbsr(H, k), cfg.dim)
+    for Y in (Y1, Y2):
+        assert (np.abs(Y.cpu().numpy() - ref) <= 1e-5 * refabs + 1e-6).all()
+    dg.close()
