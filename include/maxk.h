@@ -155,6 +155,16 @@ MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void
                            int32_t dim, int32_t k, float* d_dXs, void* stream);
 
 /*
+ * The backward pass reading dY stored in 2 bytes (value_type MAXK_VALUE_BF16 or _F16, patterns in uint16_t
+ * [N x dim]; MAXK_VALUE_F32 makes it the plain call).  The sampled gather of Alg. 2 / Eq. 3 moves whole cache
+ * lines of dY rows, so the row length in bytes is what the kernel's time follows.  Values are widened exactly;
+ * products and sums are fp32 and d_dXs is fp32, so the result meets the bound of maxk_sspmm_bwd against the
+ * definition evaluated on the 16-bit values.  Rounding fp32 gradients to 16 bits is the caller's decision.
+ */
+MAXK_API maxk_status maxk_sspmm_bwd_narrow(maxk_graph* g, const void* d_dY, int32_t value_type, const void* d_sp_index,
+                                           int32_t index_bytes, int32_t dim, int32_t k, float* d_dXs, void* stream);
+
+/*
  * MaxK backward (Sec. 3.1 definition, part (ii): the gradient keeps the sparsity pattern of the
  * forward pass): d_dense[i, sp_index[i,t]] = d_values[i,t], every other entry of d_dense[N x dim] = 0.
  * d_values is fp32 [N x k] (the dXs of maxk_sspmm_bwd).  Columns of a row must be distinct.

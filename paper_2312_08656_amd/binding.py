@@ -16,7 +16,8 @@ VALUE_F32, VALUE_BF16, VALUE_F16 = 0, 1, 2
 EXPORTS = (
     "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode", "maxk_graph_bwd_choice",
     "maxk_graph_info",
-    "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_topk_cbsr_narrow", "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
+    "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_topk_cbsr_narrow", "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd",
+    "maxk_sspmm_bwd_narrow", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
     "maxk_last_hip_error", "maxk_version", "maxk_fwd_private_copies",
 )
 
@@ -51,11 +52,12 @@ def load_library() -> ctypes.CDLL:
     lib.maxk_topk_cbsr_narrow.argtypes = [vp, i64, i32, i32, vp, i32, vp, i32, vp]
     lib.maxk_spgemm_fwd_narrow.argtypes = [vp, vp, i32, vp, i32, i32, i32, vp, vp]
     lib.maxk_sspmm_bwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.maxk_sspmm_bwd_narrow.argtypes = [vp, vp, i32, vp, i32, i32, i32, vp, vp]
     lib.maxk_cbsr_scatter.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp]
     lib.spmm_baseline.argtypes = [vp, vp, i32, vp, vp]
     for name in ("maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode",
                  "maxk_graph_info", "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_topk_cbsr_narrow",
-                 "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd", "maxk_cbsr_scatter",
+                 "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd", "maxk_sspmm_bwd_narrow", "maxk_cbsr_scatter",
                  "spmm_baseline",
                  "maxk_last_hip_error", "maxk_version"):
         getattr(lib, name).restype = i32
@@ -215,6 +217,20 @@ def maxk_sspmm_bwd(g: MaxKGraph, dY: torch.Tensor, sp_index: torch.Tensor, dXs: 
     _check(load_library().maxk_sspmm_bwd(g.handle, _dev(dY, torch.float32, "dY"),
                                          _dev(sp_index, sp_index.dtype, "sp_index"), ib, dim, k,
                                          _dev(dXs, torch.float32, "dXs"), _stream()), "maxk_sspmm_bwd")
+
+
+def maxk_sspmm_bwd_narrow(g: MaxKGraph, dY: torch.Tensor, sp_index: torch.Tensor, dXs: torch.Tensor) -> None:
+    """As maxk_sspmm_bwd with dY in its own dtype (bfloat16, float16 or float32); dXs stays fp32."""
+    N, dim = dY.shape
+    k = sp_index.shape[1]
+    if dY.dtype not in _VALUE_TYPE:
+        raise MaxKError("maxk_sspmm_bwd_narrow: dY must be float32, bfloat16 or float16")
+    if N != g.N or tuple(sp_index.shape) != (N, k) or tuple(dXs.shape) != (N, k):
+        raise MaxKError("maxk_sspmm_bwd_narrow: shape mismatch")
+    ib = _INDEX_BYTES[sp_index.dtype]
+    _check(load_library().maxk_sspmm_bwd_narrow(g.handle, _dev(dY, dY.dtype, "dY"), _VALUE_TYPE[dY.dtype],
+                                                _dev(sp_index, sp_index.dtype, "sp_index"), ib, dim, k,
+                                                _dev(dXs, torch.float32, "dXs"), _stream()), "maxk_sspmm_bwd_narrow")
 
 
 def maxk_cbsr_scatter(values: torch.Tensor, sp_index: torch.Tensor, dense: torch.Tensor) -> None:

@@ -134,21 +134,22 @@ int fwd_private_copies(int k);  // output-row copies the forward kernel keeps fo
 maxk_status launch_spmm(const ItemList& items, const int32_t* col, const float* val, const float* H, int dim,
                         float* Y, float* partials, hipStream_t s);
 
-maxk_status launch_bwd_pull(const ItemList& csc_items, const int32_t* csc_src, const float* csc_val, const float* dY,
-                            const void* sp_index, int index_bytes, int dim, int k, float* dXs, float* partials,
-                            hipStream_t s);
+// backward launchers: `dY` holds value_store_t<value_type> elements (fp32, or bf16 / fp16 patterns)
+maxk_status launch_bwd_pull(const ItemList& csc_items, const int32_t* csc_src, const float* csc_val, const void* dY,
+                            int value_type, const void* sp_index, int index_bytes, int dim, int k, float* dXs,
+                            float* partials, hipStream_t s);
 
-maxk_status launch_bwd_push(const ItemList& items, const int32_t* col, const float* val, const float* dY,
-                            const void* sp_index, int index_bytes, int64_t N, int dim, int k, float* dXs,
-                            hipStream_t s);
+maxk_status launch_bwd_push(const ItemList& items, const int32_t* col, const float* val, const void* dY,
+                            int value_type, const void* sp_index, int index_bytes, int64_t N, int dim, int k,
+                            float* dXs, hipStream_t s);
 
 maxk_status launch_bwd_expand_reduce(const ItemList& csr_items, const int32_t* col, const float* val,
-                                     const ItemList& csc_items, const uint32_t* csc_entry, const float* dY,
-                                     const void* sp_index, int index_bytes, int dim, int k, float* expand,
-                                     float* dXs, float* partials, hipStream_t s);
+                                     const ItemList& csc_items, const uint32_t* csc_entry, const void* dY,
+                                     int value_type, const void* sp_index, int index_bytes, int dim, int k,
+                                     float* expand, float* dXs, float* partials, hipStream_t s);
 
-maxk_status launch_bwd_slab_pull(const SlabSet& S, const float* dY, const void* sp_index, int index_bytes, int64_t N,
-                                 int dim, int k, float* dXs, hipStream_t s);
+maxk_status launch_bwd_slab_pull(const SlabSet& S, const void* dY, int value_type, const void* sp_index,
+                                 int index_bytes, int64_t N, int dim, int k, float* dXs, hipStream_t s);
 
 // shared by the push and slab kernels: p[0..n) = 0
 maxk_status launch_fill_zero(float* p, int64_t n, hipStream_t s);

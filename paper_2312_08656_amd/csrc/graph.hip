@@ -36,7 +36,8 @@ struct maxk_graph {
     int64_t partial_floats = 0;
     float* d_expand = nullptr;  // per-entry contributions of the expand/reduce backward kernel (nnz * k floats)
     int64_t expand_floats = 0;
-    maxk::SlabSet slabs;        // built on demand for one slab height at a time
+    maxk::SlabSet slabs;        // built on demand for one slab height at a time (fp32 dY)
+    maxk::SlabSet slabs16;      // the same for 16-bit dY, whose rows are half as long
     char* d_packed = nullptr;   // forward kernel's per-call repack of a small-k CBSR (one record per node)
     int64_t packed_bytes = 0;
     int64_t max_degree = 0;
@@ -321,9 +322,8 @@ __global__ __launch_bounds__(256) void fill_i64_kernel(int64_t* __restrict__ p, 
 }
 
 // Regroups A^T by slabs of `slab_rows` source rows (see SlabSet).  Synchronises the device.
-maxk_status build_slabs(maxk_graph* g, int32_t slab_rows)
+maxk_status build_slabs(maxk_graph* g, SlabSet& S, int32_t slab_rows)
 {
-    SlabSet& S = g->slabs;
     if (S.slab_rows == slab_rows) return MAXK_OK;
     MAXK_HIP_TRY(hipDeviceSynchronize());
     free_slabs(S);
@@ -431,10 +431,10 @@ maxk_status build_slabs(maxk_graph* g, int32_t slab_rows)
 }
 
 // Slab height for hidden width `dim`: a slab of dY should sit comfortably inside one XCD's 4 MB L2.
-int32_t slab_rows_for(int dim)
+int32_t slab_rows_for(int dim, int val_bytes = 4)
 {
     const int kb = env_int("MAXK_SLAB_KB", 3584, 64, 1 << 20);
-    const int64_t rows = (int64_t)kb * 1024 / ((int64_t)dim * 4);
+    const int64_t rows = (int64_t)kb * 1024 / ((int64_t)dim * val_bytes);
     return (int32_t)std::max<int64_t>(rows, 64);
 }
 
@@ -479,14 +479,15 @@ maxk_status ensure_expand(maxk_graph* g, int k)
 // (slab, destination) visit, so it needs several in-entries per visit: dense neighbourhoods.
 // Otherwise: expand/reduce moves 8k bytes per stored entry through HBM, plain pull touches about
 // min(k, dim/32) cache lines of a dY row per entry whatever k is, so pull wins once k is large.
-int auto_bwd_mode(const maxk_graph* g, int dim, int k)
+int auto_bwd_mode(const maxk_graph* g, int dim, int k, int val_bytes = 4)
 {
-    const double n_slabs = std::ceil((double)g->N / slab_rows_for(dim));
+    const double n_slabs = std::ceil((double)g->N / slab_rows_for(dim, val_bytes));
     const double entries_per_visit = (double)g->nnz / std::max(1.0, (double)g->N * n_slabs);
     if (entries_per_visit >= 2.0 && n_slabs * (double)g->N < 1.8e19) return MAXK_BWD_SLAB_PULL;
     // expected cache lines of a dY row touched by k sorted columns; measured crossover on four graphs:
     // expand/reduce (8k bytes per entry) beats pull (lines * 128 bytes per entry) while 8k < 44 * lines
-    const double lines = dim <= 32 ? 1.0 : (dim / 32.0) * (1.0 - std::pow(1.0 - 32.0 / dim, (double)k));
+    const double per_line = 128.0 / val_bytes;  // dY elements per cache line
+    const double lines = dim <= per_line ? 1.0 : (dim / per_line) * (1.0 - std::pow(1.0 - per_line / dim, (double)k));
     const double pull_cost = lines * 128.0 / 2.9;
     const double expand_cost = 8.0 * k;
     const bool fits = (double)g->nnz * k * 4.0 <= 96e9;
@@ -576,6 +577,7 @@ MAXK_API maxk_status maxk_graph_destroy(maxk_graph* g)
     (void)hipFree(g->d_expand);
     (void)hipFree(g->d_packed);
     free_slabs(g->slabs);
+    free_slabs(g->slabs16);
     (void)hipFree(g->d_partials);
     delete g;
     return MAXK_OK;
@@ -599,7 +601,7 @@ MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k)
         }
     }
     const int mode = g->bwd_mode == MAXK_BWD_AUTO ? auto_bwd_mode(g, dim, k) : g->bwd_mode;
-    if (mode == MAXK_BWD_SLAB_PULL) return build_slabs(g, slab_rows_for(dim));
+    if (mode == MAXK_BWD_SLAB_PULL) return build_slabs(g, g->slabs, slab_rows_for(dim));
     return mode == MAXK_BWD_EXPAND_REDUCE ? ensure_expand(g, k) : MAXK_OK;
 }
 
@@ -681,36 +683,45 @@ MAXK_API maxk_status maxk_spgemm_fwd(maxk_graph* g, const float* d_sp_data, cons
     return maxk_spgemm_fwd_narrow(g, d_sp_data, MAXK_VALUE_F32, d_sp_index, index_bytes, dim, k, d_Y, stream);
 }
 
-MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void* d_sp_index, int32_t index_bytes, int32_t dim,
-                           int32_t k, float* d_dXs, void* stream)
+MAXK_API maxk_status maxk_sspmm_bwd_narrow(maxk_graph* g, const void* d_dY, int32_t value_type, const void* d_sp_index,
+                                           int32_t index_bytes, int32_t dim, int32_t k, float* d_dXs, void* stream)
 {
     if (!g || dim < 1 || k < 1 || k > dim || bad_index_bytes(index_bytes, dim)) return MAXK_INVALID_ARGUMENT;
+    if (value_type < MAXK_VALUE_F32 || value_type > MAXK_VALUE_F16) return MAXK_INVALID_ARGUMENT;
     if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
     if (g->N == 0) return MAXK_OK;
     if (!d_dY || !d_sp_index || !d_dXs) return MAXK_INVALID_ARGUMENT;
-    if (!aligned(d_dY, 4) || !aligned(d_dXs, 4) || !aligned(d_sp_index, (size_t)index_bytes))
+    const int vb = value_bytes(value_type);
+    if (!aligned(d_dY, (size_t)vb) || !aligned(d_dXs, 4) || !aligned(d_sp_index, (size_t)index_bytes))
         return MAXK_INVALID_ARGUMENT;
     maxk_status st = ensure_workspace(g, dim, k);
     if (st != MAXK_OK) return st;
     int mode = g->bwd_mode;
-    if (mode == MAXK_BWD_AUTO) mode = auto_bwd_mode(g, dim, k);
+    if (mode == MAXK_BWD_AUTO) mode = auto_bwd_mode(g, dim, k, vb);
     if (mode == MAXK_BWD_SLAB_PULL) {
-        st = build_slabs(g, slab_rows_for(dim));
+        SlabSet& S = vb == 4 ? g->slabs : g->slabs16;
+        st = build_slabs(g, S, slab_rows_for(dim, vb));
         if (st != MAXK_OK) return st;
-        return launch_bwd_slab_pull(g->slabs, d_dY, d_sp_index, index_bytes, g->N, dim, k, d_dXs, (hipStream_t)stream);
+        return launch_bwd_slab_pull(S, d_dY, value_type, d_sp_index, index_bytes, g->N, dim, k, d_dXs, (hipStream_t)stream);
     }
     if (mode == MAXK_BWD_EXPAND_REDUCE) {
         st = ensure_expand(g, k);
         if (st != MAXK_OK) return st;
-        return launch_bwd_expand_reduce(g->csr_items, g->d_col, g->d_val, g->csc_items, g->d_csc_entry, d_dY,
+        return launch_bwd_expand_reduce(g->csr_items, g->d_col, g->d_val, g->csc_items, g->d_csc_entry, d_dY, value_type,
                                         d_sp_index, index_bytes, dim, k, g->d_expand, d_dXs, g->d_partials,
                                         (hipStream_t)stream);
     }
     if (mode == MAXK_BWD_PULL_CSC)
-        return launch_bwd_pull(g->csc_items, g->d_csc_src, g->d_csc_val, d_dY, d_sp_index, index_bytes, dim, k, d_dXs,
-                               g->d_partials, (hipStream_t)stream);
-    return launch_bwd_push(g->csr_items, g->d_col, g->d_val, d_dY, d_sp_index, index_bytes, g->N, dim, k, d_dXs,
+        return launch_bwd_pull(g->csc_items, g->d_csc_src, g->d_csc_val, d_dY, value_type, d_sp_index, index_bytes, dim, k,
+                               d_dXs, g->d_partials, (hipStream_t)stream);
+    return launch_bwd_push(g->csr_items, g->d_col, g->d_val, d_dY, value_type, d_sp_index, index_bytes, g->N, dim, k, d_dXs,
                            (hipStream_t)stream);
+}
+
+MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void* d_sp_index, int32_t index_bytes, int32_t dim,
+                           int32_t k, float* d_dXs, void* stream)
+{
+    return maxk_sspmm_bwd_narrow(g, d_dY, MAXK_VALUE_F32, d_sp_index, index_bytes, dim, k, d_dXs, stream);
 }
 
 MAXK_API maxk_status maxk_cbsr_scatter(const float* d_values, const void* d_sp_index, int32_t index_bytes, int64_t N,

@@ -119,10 +119,15 @@ def check_spmm(dg, H, H_dev, rows=None):
 _NARROW = {"bf16": (torch.bfloat16, 2.0 ** -8), "f16": (torch.float16, 2.0 ** -11)}
 
 
-def check_narrow(dg, H_dev, k, index_bytes, ref_cbsr, dim, rows=None):
+def _bits_to_dev(bits, dtype):
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(dtype)
+
+
+def check_narrow(dg, H_dev, dY, k, index_bytes, ref_cbsr, dim, rows=None):
     """16-bit CBSR values: top-k writes the oracle's rounding of the fp32 values bit for bit (same indices);
     the forward pass on them meets the usual bound against the oracle run on the widened values, and stays
-    within the format's rounding error of the fp32 result."""
+    within the format's rounding error of the fp32 result.  16-bit dY: every backward kernel meets the usual
+    bound against the oracle run on the widened dY."""
     g = dg.host
     N = g.N
     ref32, refabs32 = oracle.spgemm_fwd(g.rowptr, g.col, g.val, ref_cbsr[0], ref_cbsr[1], dim, rows=rows)
@@ -150,6 +155,22 @@ def check_narrow(dg, H_dev, k, index_bytes, ref_cbsr, dim, rows=None):
         drift = np.abs(got.astype(np.float64) - ref32)
         assert np.all(drift <= (half_ulp + 1e-5) * refabs32 + 2e-6), f"{vt}: forward drifts from fp32 by more than rounding"
         worst[vt] = ratio
+        # backward pass reading dY in this format (the rounding of dY is the oracle's, done on the CPU)
+        dY_bits = oracle.narrow(dY, vt)
+        dY16 = _bits_to_dev(dY_bits, dtype)
+        refb, refbabs = oracle.sspmm_bwd(g.rowptr, g.col, g.val, oracle.widen(dY_bits, vt), ref_cbsr[1], nodes=rows)
+        sp_index32 = sp_index
+        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_SLAB_PULL, maxk.BWD_AUTO):
+            dg.handle.set_bwd_mode(mode)
+            dXs = torch.full((N, k), float("nan"), dtype=torch.float32, device="cuda")
+            maxk.maxk_sspmm_bwd_narrow(dg.handle, dY16, sp_index32, dXs)
+            torch.cuda.synchronize()
+            assert bool(torch.isfinite(dXs).all()), f"{vt}: backward (mode {mode}) left non-finite / unwritten output"
+            gotb = dXs.cpu().numpy() if rows is None else dXs[torch.from_numpy(rows).cuda()].cpu().numpy()
+            ok, rb = within_bound(gotb, refb, refbabs)
+            assert ok, f"{vt}: backward (mode {mode}) outside the bound (worst err/bound = {rb:.3f})"
+            worst[vt] = max(worst[vt], rb)
+        dg.handle.set_bwd_mode(maxk.BWD_AUTO)
     return worst
 
 
@@ -186,5 +207,5 @@ def full_pass(dg, H, dY, k, index_bytes, sampled, seed=0, n_random=1500, spmm=Tr
         rs = check_spmm(dg, H, H_dev, rows)
         say(f"    dense SpMM ok, worst err/bound {rs:.3f} ({time.time() - t0:.1f}s)")
     if narrow:
-        rn = check_narrow(dg, H_dev, k, index_bytes, ref, dim, rows)
+        rn = check_narrow(dg, H_dev, dY, k, index_bytes, ref, dim, rows)
         say(f"    16-bit values ok, worst err/bound {rn} ({time.time() - t0:.1f}s)")

@@ -59,6 +59,7 @@ def test_invalid_arguments_are_rejected_without_touching_the_device(lib):
     assert lib.maxk_topk_cbsr_narrow(fake, 10, 64, 8, odd, 0, fake, 1, None) == INVALID  # fp32 values need 4
     assert lib.maxk_topk_cbsr_narrow(None, 0, 64, 8, None, 2, None, 1, None) == 0
     assert lib.maxk_spgemm_fwd_narrow(None, fake, 1, fake, 1, 64, 8, fake, None) == INVALID
+    assert lib.maxk_sspmm_bwd_narrow(None, fake, 1, fake, 1, 64, 8, fake, None) == INVALID
     # graph handle: null outputs / handles
     assert lib.maxk_graph_create(None, 1, 1, fake, fake, fake, None) == INVALID
     h = ctypes.c_void_p()
