@@ -225,6 +225,11 @@ def main() -> int:
                             f"{tag}_hbm_frac": round(b["bwd"] / (tb * 1e-3) / 8e12, 4),
                             f"{tag}_speedup_vs_spmm": round(spmm_ms / tb, 2)})
             gr.set_bwd_mode(maxk.BWD_AUTO)
+            # the same backward pass reading dY stored as bf16 (fp32 products and sums; not the headline)
+            dY16 = dYd.to(torch.bfloat16)
+            t16, _ = timeit(lambda: maxk.maxk_sspmm_bwd_narrow(gr, dY16, si, dx), max(3, args.sweep_reps // 2), warm=1)
+            row.update({"bwd_bf16_dY_ms": round(t16, 4)})
+            del dY16
             tb, _ = timeit(lambda: maxk.maxk_sspmm_bwd(gr, dYd, si, dx), args.sweep_reps, warm=1)
             row.update({"bwd_auto_kernel": gr.bwd_choice(dim, k),
                         "bwd_ms": round(tb, 4), "bwd_edges_k_per_s": nnz * k / (tb * 1e-3),

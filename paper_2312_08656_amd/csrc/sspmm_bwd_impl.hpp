@@ -318,7 +318,7 @@ maxk_status launch_expand_i(const ItemList& L, const int32_t* col, const float* 
 
 // ------------------------------------------------------------- slab pull ----
 
-// dY[row * dim + col] with the element offset held in 32 bits when OFF32 (the launcher checks
+// dY[row * dim + col] with the byte offset held in 32 bits when OFF32 (the launcher checks
 // that the whole of dY spans less than 4 GiB): one SGPR base + 32-bit lane offsets instead of
 // 64-bit lane addresses, which is what keeps the kernel at 8 waves per SIMD.
 template <bool OFF32, int VT>
@@ -327,7 +327,17 @@ __device__ __forceinline__ float load_sampled(const value_store_t<VT>* __restric
     using T = value_store_t<VT>;
     if constexpr (OFF32) {
         const uint32_t byte_off = ((uint32_t)row * (uint32_t)dim + (uint32_t)col) * (uint32_t)sizeof(T);
-        return widen_value<VT>(*reinterpret_cast<const T*>(reinterpret_cast<const char*>(dY) + byte_off));
+        if constexpr (sizeof(T) == 4) {
+            return widen_value<VT>(*reinterpret_cast<const T*>(reinterpret_cast<const char*>(dY) + byte_off));
+        } else {
+            // 16-bit elements: fetch the aligned dword that holds the element and pick the half.  Two-byte
+            // gathers were measured far slower than dword gathers here (15.8 against 9.6 ms at k = 128 for half
+            // the cache lines).  The launcher takes this path only when dY is 4-byte aligned and holds an even
+            // number of elements, so the dword never reaches past the array.
+            const uint32_t w = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(dY) + (byte_off & ~3u));
+            if constexpr (VT == MAXK_VALUE_BF16) return __uint_as_float((byte_off & 2u) ? (w & 0xFFFF0000u) : (w << 16));
+            else return widen_value<VT>((uint16_t)((byte_off & 2u) ? (w >> 16) : (w & 0xFFFFu)));
+        }
     } else {
         return widen_value<VT>(dY[(int64_t)row * dim + col]);
     }
@@ -520,7 +530,8 @@ template <int VT, typename IdxT>
 maxk_status launch_slab_i(const SlabSet& S, const value_store_t<VT>* dY, const IdxT* sp_index, int64_t N, int dim, int k,
                           float* dXs, hipStream_t s)
 {
-    const bool off32 = N * (int64_t)dim * (int64_t)sizeof(value_store_t<VT>) <= 0xFFFFFFFFll;
+    const bool off32 = N * (int64_t)dim * (int64_t)sizeof(value_store_t<VT>) <= 0xFFFFFFFFll &&
+                       (sizeof(value_store_t<VT>) == 4 || (aligned(dY, 4) && (N * (int64_t)dim) % 2 == 0));
     // positions per lane, measured on the dense workload (ms at k = 8 / 16 / 32 / 64 / 128):
     //   1: 3.69 / 4.71 / 5.79 / 8.32 / 13.8     2: 3.83 / 4.83 / 5.57 / 6.75 / 14.5     4: 4.47 / 5.38 / 6.21 / 6.84 / 9.63
     if (k <= 16)
