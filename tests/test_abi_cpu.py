@@ -96,3 +96,12 @@ def test_forward_private_copies_never_collide(lib):
     assert lib.maxk_fwd_private_copies(0) < 0
     # and it is not wasteful for the benchmark's k values
     assert [lib.maxk_fwd_private_copies(k) for k in (8, 16, 32, 64, 96, 128, 192)] == [8, 4, 2, 1, 2, 1, 1]
+
+
+def test_every_kernel_source_is_in_the_build():
+    """A .hip file that the build script does not list would silently drop its kernels from libmaxk.so."""
+    from pathlib import Path
+
+    from paper_2312_08656_amd import build
+    on_disk = sorted(p.name for p in (Path(build.__file__).parent / "csrc").glob("*.hip"))
+    assert on_disk == sorted(build.SOURCES)
