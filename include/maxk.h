@@ -25,6 +25,10 @@
  *     validated by the compute calls (NaN in H, column ids outside [0,N) and
  *     sp_index outside [0,dim) are contract violations).
  *   - Calls on one maxk_graph must not overlap in time (they share its workspace).
+ *   - Tuning knobs read from the environment (results never depend on them): MAXK_CHUNK (entries per
+ *     work item, default 2048, read by maxk_graph_create), MAXK_SLAB_KB (KiB of dY per slab of the slab-pull
+ *     backward kernel, default 3584), MAXK_FWD_PACK_MAX (largest CBSR row in bytes that the forward pass
+ *     repacks into one record per node, default 96).
  */
 #ifndef MAXK_H
 #define MAXK_H
