@@ -83,6 +83,13 @@ __global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict_
             v[c * 4 + 0] = x.x; v[c * 4 + 1] = x.y; v[c * 4 + 2] = x.z; v[c * 4 + 3] = x.w;
 #pragma unroll
             for (int j = 0; j < 4; ++j) key[c * 4 + j] = in ? order_key(v[c * 4 + j]) : 0u;
+        } else if constexpr (V == 2) {
+            float2 x = make_float2(0.f, 0.f);
+            const bool in = base < dim;  // dim % 2 == 0 on this path
+            if (in) x = *reinterpret_cast<const float2*>(h + base);
+            v[c * 2 + 0] = x.x; v[c * 2 + 1] = x.y;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) key[c * 2 + j] = in ? order_key(v[c * 2 + j]) : 0u;
         } else {
 #pragma unroll
             for (int j = 0; j < V; ++j) {
@@ -215,10 +222,16 @@ maxk_status launch_topk(const float* H, int64_t N, int dim, int k, void* sp_data
                         int index_bytes, hipStream_t s)
 {
     if (N == 0) return MAXK_OK;
-    const bool vec = (dim % 4 == 0) && aligned(H, 16);
-    if (vec) {
-        if (dim <= 256) return launch_e<4, 4>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+    // E values per lane in chunks of V consecutive columns (one 4*V-byte load each).  The scalar work of the
+    // descent grows with E, so E is kept at ceil(dim / 64) where a vector width divides it.
+    const bool vec4 = (dim % 4 == 0) && aligned(H, 16);
+    const bool vec2 = (dim % 2 == 0) && aligned(H, 8);
+    if (vec2 && dim > 64 && dim <= 128) return launch_e<2, 2>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+    if (vec4 && dim <= 256) return launch_e<4, 4>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+    if (vec2 && dim > 256 && dim <= 384) return launch_e<6, 2>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+    if (vec4) {
         if (dim <= 512) return launch_e<8, 4>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
+        if (dim <= 768) return launch_e<12, 4>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
         return launch_e<16, 4>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);
     }
     if (dim <= 64) return launch_e<1, 1>(H, N, dim, k, sp_data, value_type, sp_index, index_bytes, s);

@@ -72,7 +72,7 @@ def test_tiny_configs_full_compare(name):
 
 
 @pytest.mark.parametrize("dim,k,ib", [(6, 3, 1), (37, 5, 1), (100, 100, 2), (256, 255, 1), (384, 96, 2), (512, 7, 4),
-                                       (1024, 128, 2), (64, 64, 1), (130, 33, 1), (1024, 3, 2)])
+                                       (1024, 128, 2), (64, 64, 1), (130, 33, 1), (1024, 3, 2), (768, 40, 2), (96, 24, 1)])
 def test_odd_shapes_and_index_widths(dim, k, ib):
     # signed general weights on a directed graph: exercises the transpose and cancellation
     # ((1024, 3): too many private output-row copies for LDS, the forward takes its single-copy fallback)
@@ -110,6 +110,14 @@ def test_topk_ties_signed_zero_and_infinities():
     for k in (31, 32, 128, 256):
         sp_data, sp_index = gpu_topk(to_dev(H256), k, 1)
         check_topk(H256, k, sp_data, sp_index)
+    # every register layout of the kernel (values per lane x vector width): widths 96..1000
+    for dim in (96, 128, 130, 320, 640, 768, 1000):
+        Hw = synth.normal_matrix(1500, dim, seed=dim)
+        synth.add_tie_rows(Hw, seed=dim, percent=40, pool=16, const_every=8)
+        Hw[3, :] = np.float32(0.25)
+        for k in (1, dim // 3, dim - 1, dim):
+            sp_data, sp_index = gpu_topk(to_dev(Hw), k, 2)
+            check_topk(Hw, k, sp_data, sp_index)
 
 
 def test_empty_graph_empty_rows_duplicates_unsorted_columns():
