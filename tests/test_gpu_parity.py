@@ -380,3 +380,29 @@ def test_narrow_entry_points_with_fp32_values_are_the_plain_calls():
     for Y in (Y1, Y2):
         assert (np.abs(Y.cpu().numpy() - ref) <= 1e-5 * refabs + 1e-6).all()
     dg.close()
+
+
+def test_graph_create_rejects_bad_structure():
+    """Column ids outside [0, N), a rowptr that does not start at 0 / end at nnz / decreases: the handle is not
+    created and nothing is read through the bad ids (the column check is a bounded histogram)."""
+    rowptr = np.array([0, 2, 3, 5], np.int32)
+    col = np.array([0, 2, 1, 0, 1], np.int32)
+    val = np.ones(5, np.float32)
+    ok = maxk.maxk_graph_create(to_dev(rowptr), to_dev(col), to_dev(val))
+    ok.destroy()
+    for bad_col in (3, -1, 2 ** 31 - 1):
+        c = col.copy()
+        c[3] = bad_col
+        with pytest.raises(maxk.MaxKError):
+            maxk.maxk_graph_create(to_dev(rowptr), to_dev(c), to_dev(val))
+    for bad_ptr in ([1, 2, 3, 5], [0, 2, 3, 4], [0, 3, 2, 5]):
+        with pytest.raises(maxk.MaxKError):
+            maxk.maxk_graph_create(to_dev(np.array(bad_ptr, np.int32)), to_dev(col), to_dev(val))
+    # the library is still usable afterwards
+    g2 = maxk.maxk_graph_create(to_dev(rowptr), to_dev(col), to_dev(val))
+    Y = torch.empty((3, 4), device="cuda")
+    H = to_dev(np.arange(12, dtype=np.float32).reshape(3, 4))
+    maxk.spmm_baseline(g2, H, Y)
+    want = np.array([[0 + 8, 1 + 9, 2 + 10, 3 + 11], [4, 5, 6, 7], [0 + 4, 1 + 5, 2 + 6, 3 + 7]], np.float32)
+    assert np.array_equal(Y.cpu().numpy(), want)
+    g2.destroy()
