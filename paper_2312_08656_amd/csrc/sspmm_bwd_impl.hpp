@@ -357,6 +357,7 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
                                                          const int32_t* __restrict__ visit_begin, int64_t v_begin,
                                                          int64_t v_end, const int32_t* __restrict__ long_visit,
                                                          int64_t l_begin, int64_t l_end, int n_long_blocks,
+                                                         int long_pad, int64_t tasks_per_xcd,
                                                          const int32_t* __restrict__ slab_src,
                                                          const float* __restrict__ slab_val,
                                                          const value_store_t<VT>* __restrict__ dY,
@@ -419,10 +420,15 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
     // one address still costs one look-up per 4 lanes.  So everything that is the same for the lanes of a
     // visit (header, sources, values) is fetched by as few lanes as possible -- lane u of the group fetches
     // entry u -- and handed round with lane shuffles, which do not go through the L1.
-    const int64_t first = (int64_t)(blockIdx.x - n_long_blocks) * G;
-    const int64_t stride = (int64_t)(gridDim.x - n_long_blocks) * G;
+    // Workgroup b runs on XCD b % 8 (measured).  The visits of the launch are cut into 8 contiguous ranges, one per
+    // XCD, so that the streamed arrays (headers, entries, CBSR indices: several visits per cache line) are pulled
+    // into one L2 only instead of into up to four.  Blocks [n_long_blocks, long_pad) idle so that the ranges line up.
+    const int64_t wg = (int64_t)blockIdx.x - long_pad;
+    if (wg < 0) return;
+    const int64_t v0 = v_begin + ((wg & 7) * tasks_per_xcd + (wg >> 3)) * G;
+    if ((wg >> 3) >= tasks_per_xcd || v0 >= v_end) return;
     const int gbase = g * LPD;  // first lane of this lane group
-    for (int64_t v0 = v_begin + first; v0 < v_end; v0 += stride) {  // uniform; one step when the grid covers all visits
+    {
         const int64_t v = v0 + g;
         const bool have = v < v_end;
         int b, e;
@@ -493,7 +499,6 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
 // One wave step per workgroup measured best (6.8 -> 6.4 ms at k=32 against a grid capped at the number of
 // resident wavefronts): the hardware dispatcher hides the two dependent loads that open a visit better
 // than a software loop over visits does.
-inline int64_t slab_grid_cap() { return 0x7FFF0000ll; }
 
 template <int VEC, bool OFF32, int VT, typename IdxT>
 maxk_status launch_slab_t(const SlabSet& S, const value_store_t<VT>* dY, const IdxT* sp_index, int dim, int k, float* dXs,
@@ -508,10 +513,12 @@ maxk_status launch_slab_t(const SlabSet& S, const value_store_t<VT>* dY, const I
 #define MAXK_SLAB(LPD)                                                                                             \
     do {                                                                                                           \
         const int64_t tasks = (ve - vb + (kWave / LPD) - 1) / (kWave / LPD);                                       \
-        const unsigned grid = (unsigned)std::min<int64_t>(tasks, slab_grid_cap());                                 \
-        hipLaunchKernelGGL((bwd_slab_kernel<VEC, LPD, OFF32, VT, IdxT>), dim3(grid + (unsigned)nlb), dim3(kWave), 0, s,      \
-                           S.d_visit_node, S.d_visit_begin, vb, ve, S.d_long_visit, lb, le, nlb, S.d_src, S.d_val, \
-                           dY, sp_index, dim, k, dXs);                                                             \
+        const int64_t per_xcd = (tasks + 7) / 8;                                                                   \
+        const int long_pad = (nlb + 7) & ~7;                                                                       \
+        if (per_xcd * 8 + long_pad > 0x7FFFFFFFll) return MAXK_UNSUPPORTED;                                       \
+        hipLaunchKernelGGL((bwd_slab_kernel<VEC, LPD, OFF32, VT, IdxT>), dim3((unsigned)(per_xcd * 8 + long_pad)), \
+                           dim3(kWave), 0, s, S.d_visit_node, S.d_visit_begin, vb, ve, S.d_long_visit, lb, le, nlb, \
+                           long_pad, per_xcd, S.d_src, S.d_val, dY, sp_index, dim, k, dXs);                         \
     } while (0)
         if (kq <= 1) MAXK_SLAB(1);
         else if (kq <= 2) MAXK_SLAB(2);
