@@ -496,6 +496,173 @@ __global__ __launch_bounds__(kWave) void bwd_slab_kernel(const int32_t* __restri
     }
 }
 
+// ---- slab pull, row-accumulating form (large k) ----
+//
+// From k = 32 up the sampled gather above spends about one L1 access per sampled element.  Here a visit
+// instead adds up WHOLE dY rows -- one 16-byte load per lane covers a 1 KB row with 16 L1 accesses -- into
+// the full row of (A^T dY)[j, :] held in registers (lane l keeps columns 4l..4l+3 of every 256-column chunk),
+// and samples that row at the destination's k columns once per visit, through LDS.  The arithmetic grows from
+// k to dim multiply-adds per entry, which the vector units absorb; cache lines per entry are those of the
+// whole row, so this form is for k large enough that the sampled form touches all of them anyway.
+// One wavefront walks VPW consecutive visits; the entries of the next visit are fetched while the rows of the
+// current one are in flight.
+// A lane's share of a dY row: 4 consecutive elements (16 bytes of fp32, 8 bytes of a 16-bit format; 16-byte pieces
+// on half the lanes were measured slower for the 16-bit formats).
+template <int VT>
+struct row_piece { using type = float4; static constexpr int n = 4; };
+template <>
+struct row_piece<MAXK_VALUE_BF16> { using type = uint2; static constexpr int n = 4; };
+template <>
+struct row_piece<MAXK_VALUE_F16> { using type = uint2; static constexpr int n = 4; };
+
+template <int VT>
+__device__ __forceinline__ void fma_piece(float (&acc)[row_piece<VT>::n], float a, typename row_piece<VT>::type x)
+{
+    if constexpr (VT == MAXK_VALUE_F32) {
+        acc[0] += a * x.x; acc[1] += a * x.y; acc[2] += a * x.z; acc[3] += a * x.w;
+    } else {
+        const uint32_t w[2] = {x.x, x.y};
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            acc[2 * i] += a * widen_value<VT>((uint16_t)(w[i] & 0xFFFFu));
+            acc[2 * i + 1] += a * widen_value<VT>((uint16_t)(w[i] >> 16));
+        }
+    }
+}
+
+constexpr int kRowAccInFlight = 8;  // dY rows a wavefront has in flight
+
+// CNT rows (entries u0 .. u0 + CNT - 1 of the batch held in src_m / val_m) loaded back to back, then added up.
+// Row number, weight and row address are wave-uniform and stay on the scalar side (lane reads into scalar
+// registers, scalar address arithmetic); the count is a template parameter so that a batch is straight-line code
+// with exactly its own loads -- padding short batches with repeated rows cost 16 L1 accesses per padded row, and
+// branches around single loads stopped the compiler from keeping a batch's rows in flight together.
+template <int CNT, int RC, int VT>
+__device__ __forceinline__ void rowacc_batch(float (&acc)[RC][row_piece<VT>::n], int32_t src_m, float val_m, int u0,
+                                             const value_store_t<VT>* __restrict__ dY, int dim, int lane,
+                                             const bool (&col_ok)[RC])
+{
+    using piece_t = typename row_piece<VT>::type;
+    constexpr int EPL = row_piece<VT>::n;
+    constexpr int CHUNK = kWave * EPL;
+    piece_t x[CNT][RC];
+    float a[CNT];
+#pragma unroll
+    for (int uu = 0; uu < CNT; ++uu) {
+        const int64_t row = __builtin_amdgcn_readlane(src_m, u0 + uu);
+        a[uu] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(val_m), u0 + uu));
+        const value_store_t<VT>* __restrict__ r = dY + row * dim + lane * EPL;
+#pragma unroll
+        for (int c = 0; c < RC; ++c) {
+            piece_t z = {};
+            if (col_ok[c]) z = *reinterpret_cast<const piece_t*>(r + c * CHUNK);
+            x[uu][c] = z;
+        }
+    }
+#pragma unroll
+    for (int uu = 0; uu < CNT; ++uu)
+#pragma unroll
+        for (int c = 0; c < RC; ++c) fma_piece<VT>(acc[c], a[uu], x[uu][c]);
+}
+
+// RC: chunks of 64 row pieces (256 columns) that cover a row
+template <int RC, int VT, typename IdxT>
+__global__ __launch_bounds__(kWave) void bwd_slab_rowacc_kernel(const int32_t* __restrict__ visit_node,
+                                                                const int32_t* __restrict__ visit_begin,
+                                                                int64_t v_begin, int64_t v_end, int visits_per_wave,
+                                                                int64_t tasks_per_xcd,
+                                                                const int32_t* __restrict__ slab_src,
+                                                                const float* __restrict__ slab_val,
+                                                                const value_store_t<VT>* __restrict__ dY,
+                                                                const IdxT* __restrict__ sp_index, int dim, int k,
+                                                                float* __restrict__ dXs)
+{
+    using piece_t = typename row_piece<VT>::type;
+    constexpr int EPL = row_piece<VT>::n;      // elements per lane and chunk
+    constexpr int CHUNK = kWave * EPL;         // columns per chunk
+    constexpr int U = kRowAccInFlight;
+    __shared__ __attribute__((aligned(16))) float row_acc[RC * CHUNK];
+    const int lane = threadIdx.x;
+    const int64_t wg = blockIdx.x;  // workgroup b runs on XCD b % 8: each XCD takes a contiguous range of visits
+    if ((wg >> 3) >= tasks_per_xcd) return;
+    const int64_t v0 = v_begin + ((wg & 7) * tasks_per_xcd + (wg >> 3)) * visits_per_wave;
+    if (v0 >= v_end) return;
+    const int nv = (int)min((int64_t)visits_per_wave, v_end - v0);  // <= 32
+    const int hdr_begin = (lane <= nv) ? visit_begin[v0 + lane] : 0;
+    const int hdr_node = (lane < nv) ? visit_node[v0 + lane] : 0;
+    bool col_ok[RC];
+#pragma unroll
+    for (int c = 0; c < RC; ++c) col_ok[c] = c * CHUNK + lane * EPL < dim;  // dim % EPL == 0 on this path
+
+    int b = __builtin_amdgcn_readfirstlane(__shfl(hdr_begin, 0));
+    int e = __builtin_amdgcn_readfirstlane(__shfl(hdr_begin, 1));
+    int32_t src_next = (lane < e - b) ? slab_src[b + lane] : 0;
+    float val_next = (lane < e - b) ? slab_val[b + lane] : 0.f;
+    for (int n = 0; n < nv; ++n) {
+        const int64_t j = __builtin_amdgcn_readfirstlane(__shfl(hdr_node, n));
+        const int cnt = e - b;
+        int32_t src_m = src_next;
+        float val_m = val_next;
+        const int b_cur = b;
+        if (n + 1 < nv) {  // the next visit's first 64 entries, fetched under this visit's row loads
+            b = e;
+            e = __builtin_amdgcn_readfirstlane(__shfl(hdr_begin, n + 2));
+            src_next = (lane < e - b) ? slab_src[b + lane] : 0;
+            val_next = (lane < e - b) ? slab_val[b + lane] : 0.f;
+        }
+        // the destination's columns and its dXs values are asked for now and used after the rows (k <= 128: two
+        // per lane are held in registers; beyond that the tail is fetched at the end)
+        int col_t[2];
+        float dx_t[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int t = lane + h * kWave;
+            col_t[h] = (t < k) ? (int)sp_index[j * k + t] : 0;
+            dx_t[h] = (t < k) ? dXs[j * k + t] : 0.f;
+        }
+        float acc[RC][EPL];
+#pragma unroll
+        for (int c = 0; c < RC; ++c)
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[c][i] = 0.f;
+        for (int p0 = 0; p0 < cnt; p0 += kWave) {
+            if (p0 > 0) {  // visits of more than 64 entries: further batches are fetched here
+                src_m = (p0 + lane < cnt) ? slab_src[b_cur + p0 + lane] : 0;
+                val_m = (p0 + lane < cnt) ? slab_val[b_cur + p0 + lane] : 0.f;
+            }
+            const int nb = min(kWave, cnt - p0);
+            for (int u0 = 0; u0 < nb; u0 += U) {
+                switch (min(nb - u0, U)) {
+                    case 1: rowacc_batch<1, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
+                    case 2: rowacc_batch<2, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
+                    case 3: rowacc_batch<3, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
+                    case 4: rowacc_batch<4, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
+                    case 5: rowacc_batch<5, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
+                    case 6: rowacc_batch<6, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
+                    case 7: rowacc_batch<7, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
+                    default: rowacc_batch<8, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
+                }
+            }
+        }
+        // the visit's share of (A^T dY)[j, :] -> LDS, then dXs[j, t] += row[sp_index[j, t]]
+#pragma unroll
+        for (int c = 0; c < RC; ++c)
+#pragma unroll
+            for (int i = 0; i < EPL; i += 4)
+                *reinterpret_cast<float4*>(row_acc + c * CHUNK + lane * EPL + i) =
+                    make_float4(acc[c][i], acc[c][i + 1], acc[c][i + 2], acc[c][i + 3]);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int t = lane + h * kWave;
+            if (t < k) dXs[j * k + t] = dx_t[h] + row_acc[col_t[h]];
+        }
+        for (int t = lane + 2 * kWave; t < k; t += kWave) {
+            const int col = (int)sp_index[j * k + t];
+            dXs[j * k + t] += row_acc[col];
+        }
+    }
+}
+
 // One wave step per workgroup measured best (6.8 -> 6.4 ms at k=32 against a grid capped at the number of
 // resident wavefronts): the hardware dispatcher hides the two dependent loads that open a visit better
 // than a software loop over visits does.
@@ -533,10 +700,38 @@ maxk_status launch_slab_t(const SlabSet& S, const value_store_t<VT>* dY, const I
     return MAXK_OK;
 }
 
+template <int RC, int VT, typename IdxT>
+maxk_status launch_slab_rowacc(const SlabSet& S, const value_store_t<VT>* dY, const IdxT* sp_index, int dim, int k,
+                               float* dXs, hipStream_t s)
+{
+    const int vpw = 4;  // consecutive visits per wavefront (4 and 8 measured alike)
+    for (int32_t sl = 0; sl < S.n_slabs; ++sl) {
+        const int64_t vb = S.h_slab_visit[sl], ve = S.h_slab_visit[sl + 1];
+        if (vb >= ve) continue;
+        const int64_t tasks = (ve - vb + vpw - 1) / vpw;
+        const int64_t per_xcd = (tasks + 7) / 8;
+        if (per_xcd * 8 > 0x7FFFFFFFll) return MAXK_UNSUPPORTED;
+        hipLaunchKernelGGL((bwd_slab_rowacc_kernel<RC, VT, IdxT>), dim3((unsigned)(per_xcd * 8)), dim3(kWave), 0, s,
+                           S.d_visit_node, S.d_visit_begin, vb, ve, vpw, per_xcd, S.d_src, S.d_val, dY, sp_index, dim, k,
+                           dXs);
+    }
+    MAXK_LAUNCH_CHECK();
+    return MAXK_OK;
+}
+
 template <int VT, typename IdxT>
 maxk_status launch_slab_i(const SlabSet& S, const value_store_t<VT>* dY, const IdxT* sp_index, int64_t N, int dim, int k,
                           float* dXs, hipStream_t s)
 {
+    // Row-accumulating form from the k where it was measured faster on the dense workload (dim 256; ms, sampled /
+    // row-accumulating): fp32 k=64 6.68 / 6.82, k=80 9.63 / 7.35, k=128 9.62 / 7.77; 16-bit dY k=16 4.1 / 5.1,
+    // k=24 5.8 / 5.1, k=128 11.6 / 5.7.  Other widths use the same ratios of k to dim.
+    const bool rowacc = sizeof(value_store_t<VT>) == 4 ? 4 * k > dim : 12 * k > dim;
+    if (rowacc && dim % 4 == 0 && aligned(dY, 16)) {
+        if (dim <= 256) return launch_slab_rowacc<1, VT>(S, dY, sp_index, dim, k, dXs, s);
+        if (dim <= 512) return launch_slab_rowacc<2, VT>(S, dY, sp_index, dim, k, dXs, s);
+        if (dim <= 1024) return launch_slab_rowacc<4, VT>(S, dY, sp_index, dim, k, dXs, s);
+    }
     const bool off32 = N * (int64_t)dim * (int64_t)sizeof(value_store_t<VT>) <= 0xFFFFFFFFll &&
                        (sizeof(value_store_t<VT>) == 4 || (aligned(dY, 4) && (N * (int64_t)dim) % 2 == 0));
     // positions per lane, measured on the dense workload (ms at k = 8 / 16 / 32 / 64 / 128):

@@ -72,7 +72,7 @@ def test_tiny_configs_full_compare(name):
 
 
 @pytest.mark.parametrize("dim,k,ib", [(6, 3, 1), (37, 5, 1), (100, 100, 2), (256, 255, 1), (384, 96, 2), (512, 7, 4),
-                                       (1024, 128, 2), (64, 64, 1), (130, 33, 1), (1024, 3, 2), (768, 40, 2), (96, 24, 1)])
+                                       (1024, 128, 2), (64, 64, 1), (130, 33, 1), (1024, 3, 2), (768, 40, 2), (96, 24, 1), (512, 200, 2), (1024, 300, 2), (260, 100, 2)])
 def test_odd_shapes_and_index_widths(dim, k, ib):
     # signed general weights on a directed graph: exercises the transpose and cancellation
     # ((1024, 3): too many private output-row copies for LDS, the forward takes its single-copy fallback)
