@@ -352,8 +352,11 @@ maxk_status build_slabs(maxk_graph* g, SlabSet& S, int32_t slab_rows)
         hipError_t _e = (expr);                                                        \
         if (_e != hipSuccess) { cleanup(); free_slabs(S); return hip_fail(_e); }       \
     } while (0)
-    MAXK_TRY_CLEAN(hipMalloc((void**)&S.d_src, sizeof(int32_t) * (size_t)nnz));
-    MAXK_TRY_CLEAN(hipMalloc((void**)&S.d_val, sizeof(float) * (size_t)nnz));
+    // 8 spare entries at the end: the row-accumulating kernel fetches entries eight at a time with scalar loads
+    MAXK_TRY_CLEAN(hipMalloc((void**)&S.d_src, sizeof(int32_t) * (size_t)(nnz + 8)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&S.d_val, sizeof(float) * (size_t)(nnz + 8)));
+    MAXK_TRY_CLEAN(hipMemsetAsync(S.d_src + nnz, 0, sizeof(int32_t) * 8, s));
+    MAXK_TRY_CLEAN(hipMemsetAsync(S.d_val + nnz, 0, sizeof(float) * 8, s));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_key, sizeof(uint64_t) * (size_t)nnz));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_key_sorted, sizeof(uint64_t) * (size_t)nnz));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_iota, sizeof(uint32_t) * (size_t)nnz));

@@ -532,13 +532,31 @@ __device__ __forceinline__ void fma_piece(float (&acc)[row_piece<VT>::n], float 
 
 constexpr int kRowAccInFlight = 8;  // dY rows a wavefront has in flight
 
-// CNT rows (entries u0 .. u0 + CNT - 1 of the batch held in src_m / val_m) loaded back to back, then added up.
-// Row number, weight and row address are wave-uniform and stay on the scalar side (lane reads into scalar
-// registers, scalar address arithmetic); the count is a template parameter so that a batch is straight-line code
-// with exactly its own loads -- padding short batches with repeated rows cost 16 L1 accesses per padded row, and
-// branches around single loads stopped the compiler from keeping a batch's rows in flight together.
-template <int CNT, int RC, int VT>
-__device__ __forceinline__ void rowacc_batch(float (&acc)[RC][row_piece<VT>::n], int32_t src_m, float val_m, int u0,
+// Eight consecutive regrouped entries (source row, weight).  Their addresses are wave-uniform, so they are fetched
+// with scalar loads into scalar registers: no vector instruction and no L1 access is spent on them.
+struct entry_batch {
+    int32_t row[kRowAccInFlight];
+    float w[kRowAccInFlight];
+};
+
+__device__ __forceinline__ entry_batch load_entry_batch(const int32_t* __restrict__ slab_src,
+                                                        const float* __restrict__ slab_val, int pos)
+{
+    entry_batch en;  // may read up to 8 entries past the last one of the launch: the arrays are padded by 8
+#pragma unroll
+    for (int i = 0; i < kRowAccInFlight; ++i) {
+        en.row[i] = slab_src[pos + i];
+        en.w[i] = slab_val[pos + i];
+    }
+    return en;
+}
+
+// CNT rows loaded back to back, then added up.  The count is a template parameter so that a batch is straight-line
+// code with exactly its own loads -- padding short batches with repeated rows cost 16 L1 accesses per padded row,
+// and branches around single loads stopped the compiler from keeping a batch's rows in flight together.
+// FULL: dim == RC * 256, every lane holds valid columns in every chunk.
+template <int CNT, int RC, bool FULL, int VT>
+__device__ __forceinline__ void rowacc_batch(float (&acc)[RC][row_piece<VT>::n], const entry_batch& en,
                                              const value_store_t<VT>* __restrict__ dY, int dim, int lane,
                                              const bool (&col_ok)[RC])
 {
@@ -546,27 +564,28 @@ __device__ __forceinline__ void rowacc_batch(float (&acc)[RC][row_piece<VT>::n],
     constexpr int EPL = row_piece<VT>::n;
     constexpr int CHUNK = kWave * EPL;
     piece_t x[CNT][RC];
-    float a[CNT];
 #pragma unroll
     for (int uu = 0; uu < CNT; ++uu) {
-        const int64_t row = __builtin_amdgcn_readlane(src_m, u0 + uu);
-        a[uu] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(val_m), u0 + uu));
-        const value_store_t<VT>* __restrict__ r = dY + row * dim + lane * EPL;
+        const value_store_t<VT>* __restrict__ r = dY + (int64_t)en.row[uu] * dim + lane * EPL;
 #pragma unroll
         for (int c = 0; c < RC; ++c) {
-            piece_t z = {};
-            if (col_ok[c]) z = *reinterpret_cast<const piece_t*>(r + c * CHUNK);
-            x[uu][c] = z;
+            if constexpr (FULL) {
+                x[uu][c] = *reinterpret_cast<const piece_t*>(r + c * CHUNK);
+            } else {
+                piece_t z = {};
+                if (col_ok[c]) z = *reinterpret_cast<const piece_t*>(r + c * CHUNK);
+                x[uu][c] = z;
+            }
         }
     }
 #pragma unroll
     for (int uu = 0; uu < CNT; ++uu)
 #pragma unroll
-        for (int c = 0; c < RC; ++c) fma_piece<VT>(acc[c], a[uu], x[uu][c]);
+        for (int c = 0; c < RC; ++c) fma_piece<VT>(acc[c], en.w[uu], x[uu][c]);
 }
 
 // RC: chunks of 64 row pieces (256 columns) that cover a row
-template <int RC, int VT, typename IdxT>
+template <int RC, bool FULL, int VT, typename IdxT>
 __global__ __launch_bounds__(kWave) void bwd_slab_rowacc_kernel(const int32_t* __restrict__ visit_node,
                                                                 const int32_t* __restrict__ visit_begin,
                                                                 int64_t v_begin, int64_t v_end, int visits_per_wave,
@@ -577,7 +596,6 @@ __global__ __launch_bounds__(kWave) void bwd_slab_rowacc_kernel(const int32_t* _
                                                                 const IdxT* __restrict__ sp_index, int dim, int k,
                                                                 float* __restrict__ dXs)
 {
-    using piece_t = typename row_piece<VT>::type;
     constexpr int EPL = row_piece<VT>::n;      // elements per lane and chunk
     constexpr int CHUNK = kWave * EPL;         // columns per chunk
     constexpr int U = kRowAccInFlight;
@@ -592,24 +610,14 @@ __global__ __launch_bounds__(kWave) void bwd_slab_rowacc_kernel(const int32_t* _
     const int hdr_node = (lane < nv) ? visit_node[v0 + lane] : 0;
     bool col_ok[RC];
 #pragma unroll
-    for (int c = 0; c < RC; ++c) col_ok[c] = c * CHUNK + lane * EPL < dim;  // dim % EPL == 0 on this path
+    for (int c = 0; c < RC; ++c) col_ok[c] = c * CHUNK + lane * EPL < dim;  // dim % 4 == 0 on this path
 
-    int b = __builtin_amdgcn_readfirstlane(__shfl(hdr_begin, 0));
-    int e = __builtin_amdgcn_readfirstlane(__shfl(hdr_begin, 1));
-    int32_t src_next = (lane < e - b) ? slab_src[b + lane] : 0;
-    float val_next = (lane < e - b) ? slab_val[b + lane] : 0.f;
+    // the entries of consecutive visits are consecutive in the regrouped arrays: one running position
+    int pos = __builtin_amdgcn_readfirstlane(__shfl(hdr_begin, 0));
+    entry_batch cur = load_entry_batch(slab_src, slab_val, pos);
     for (int n = 0; n < nv; ++n) {
         const int64_t j = __builtin_amdgcn_readfirstlane(__shfl(hdr_node, n));
-        const int cnt = e - b;
-        int32_t src_m = src_next;
-        float val_m = val_next;
-        const int b_cur = b;
-        if (n + 1 < nv) {  // the next visit's first 64 entries, fetched under this visit's row loads
-            b = e;
-            e = __builtin_amdgcn_readfirstlane(__shfl(hdr_begin, n + 2));
-            src_next = (lane < e - b) ? slab_src[b + lane] : 0;
-            val_next = (lane < e - b) ? slab_val[b + lane] : 0.f;
-        }
+        const int e = __builtin_amdgcn_readfirstlane(__shfl(hdr_begin, n + 1));
         // the destination's columns and its dXs values are asked for now and used after the rows (k <= 128: two
         // per lane are held in registers; beyond that the tail is fetched at the end)
         int col_t[2];
@@ -625,24 +633,22 @@ __global__ __launch_bounds__(kWave) void bwd_slab_rowacc_kernel(const int32_t* _
         for (int c = 0; c < RC; ++c)
 #pragma unroll
             for (int i = 0; i < EPL; ++i) acc[c][i] = 0.f;
-        for (int p0 = 0; p0 < cnt; p0 += kWave) {
-            if (p0 > 0) {  // visits of more than 64 entries: further batches are fetched here
-                src_m = (p0 + lane < cnt) ? slab_src[b_cur + p0 + lane] : 0;
-                val_m = (p0 + lane < cnt) ? slab_val[b_cur + p0 + lane] : 0.f;
+        while (pos < e) {
+            const int cnt = min(e - pos, U);
+            // the next batch (of this visit or the next one) is fetched under this batch's row loads
+            const entry_batch nxt = load_entry_batch(slab_src, slab_val, pos + cnt);
+            switch (cnt) {
+                case 1: rowacc_batch<1, RC, FULL, VT>(acc, cur, dY, dim, lane, col_ok); break;
+                case 2: rowacc_batch<2, RC, FULL, VT>(acc, cur, dY, dim, lane, col_ok); break;
+                case 3: rowacc_batch<3, RC, FULL, VT>(acc, cur, dY, dim, lane, col_ok); break;
+                case 4: rowacc_batch<4, RC, FULL, VT>(acc, cur, dY, dim, lane, col_ok); break;
+                case 5: rowacc_batch<5, RC, FULL, VT>(acc, cur, dY, dim, lane, col_ok); break;
+                case 6: rowacc_batch<6, RC, FULL, VT>(acc, cur, dY, dim, lane, col_ok); break;
+                case 7: rowacc_batch<7, RC, FULL, VT>(acc, cur, dY, dim, lane, col_ok); break;
+                default: rowacc_batch<8, RC, FULL, VT>(acc, cur, dY, dim, lane, col_ok); break;
             }
-            const int nb = min(kWave, cnt - p0);
-            for (int u0 = 0; u0 < nb; u0 += U) {
-                switch (min(nb - u0, U)) {
-                    case 1: rowacc_batch<1, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
-                    case 2: rowacc_batch<2, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
-                    case 3: rowacc_batch<3, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
-                    case 4: rowacc_batch<4, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
-                    case 5: rowacc_batch<5, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
-                    case 6: rowacc_batch<6, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
-                    case 7: rowacc_batch<7, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
-                    default: rowacc_batch<8, RC, VT>(acc, src_m, val_m, u0, dY, dim, lane, col_ok); break;
-                }
-            }
+            cur = nxt;
+            pos += cnt;
         }
         // the visit's share of (A^T dY)[j, :] -> LDS, then dXs[j, t] += row[sp_index[j, t]]
 #pragma unroll
@@ -711,9 +717,14 @@ maxk_status launch_slab_rowacc(const SlabSet& S, const value_store_t<VT>* dY, co
         const int64_t tasks = (ve - vb + vpw - 1) / vpw;
         const int64_t per_xcd = (tasks + 7) / 8;
         if (per_xcd * 8 > 0x7FFFFFFFll) return MAXK_UNSUPPORTED;
-        hipLaunchKernelGGL((bwd_slab_rowacc_kernel<RC, VT, IdxT>), dim3((unsigned)(per_xcd * 8)), dim3(kWave), 0, s,
-                           S.d_visit_node, S.d_visit_begin, vb, ve, vpw, per_xcd, S.d_src, S.d_val, dY, sp_index, dim, k,
-                           dXs);
+        if (dim == RC * 256)
+            hipLaunchKernelGGL((bwd_slab_rowacc_kernel<RC, true, VT, IdxT>), dim3((unsigned)(per_xcd * 8)), dim3(kWave), 0,
+                               s, S.d_visit_node, S.d_visit_begin, vb, ve, vpw, per_xcd, S.d_src, S.d_val, dY, sp_index,
+                               dim, k, dXs);
+        else
+            hipLaunchKernelGGL((bwd_slab_rowacc_kernel<RC, false, VT, IdxT>), dim3((unsigned)(per_xcd * 8)), dim3(kWave),
+                               0, s, S.d_visit_node, S.d_visit_begin, vb, ve, vpw, per_xcd, S.d_src, S.d_val, dY, sp_index,
+                               dim, k, dXs);
     }
     MAXK_LAUNCH_CHECK();
     return MAXK_OK;
@@ -724,9 +735,9 @@ maxk_status launch_slab_i(const SlabSet& S, const value_store_t<VT>* dY, const I
                           float* dXs, hipStream_t s)
 {
     // Row-accumulating form from the k where it was measured faster on the dense workload (dim 256; ms, sampled /
-    // row-accumulating): fp32 k=64 6.68 / 6.82, k=80 9.63 / 7.35, k=128 9.62 / 7.77; 16-bit dY k=16 4.1 / 5.1,
-    // k=24 5.8 / 5.1, k=128 11.6 / 5.7.  Other widths use the same ratios of k to dim.
-    const bool rowacc = sizeof(value_store_t<VT>) == 4 ? 4 * k > dim : 12 * k > dim;
+    // row-accumulating): fp32 k=24 5.26 / 5.39, k=32 5.42 / 5.41, k=64 6.64 / 5.76, k=128 9.62 / 6.70;
+    // 16-bit dY k=8 3.1 / 4.3, k=16 4.1 / 4.2, k=32 5.8 / 4.3, k=128 11.5 / 4.8.  Other widths use the same ratios.
+    const bool rowacc = sizeof(value_store_t<VT>) == 4 ? 8 * k >= dim : 16 * k > dim;
     if (rowacc && dim % 4 == 0 && aligned(dY, 16)) {
         if (dim <= 256) return launch_slab_rowacc<1, VT>(S, dY, sp_index, dim, k, dXs, s);
         if (dim <= 512) return launch_slab_rowacc<2, VT>(S, dY, sp_index, dim, k, dXs, s);
