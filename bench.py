@@ -33,9 +33,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # 1 GiB copy reads on the same counters: x2.0 and x1.0), from profiles/dense_k32_step_trace_and_counters.txt.
 # Keyed by (workload, k, entry point, backward mode); anything else reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dense", 32, "maxk_spgemm_fwd", None): 20.99e9,
-    ("dense", 32, "maxk_sspmm_bwd", "auto"): 13.44e9,
-    ("dense", 32, "maxk_sspmm_bwd", "slab"): 13.44e9,
+    ("dense", 32, "maxk_spgemm_fwd", None): 21.06e9,
+    ("dense", 32, "maxk_sspmm_bwd", "auto"): 10.95e9,
+    ("dense", 32, "maxk_sspmm_bwd", "slab"): 10.95e9,
 }
 
 
