@@ -1,5 +1,5 @@
 // Backward aggregation: sampled SSpMM  dXs = (A^T dY) at each row's CBSR columns
-// (Eq. 2 right; Eq. 3; prior art: Alg. 2).  Two kernels with the same result:
+// (Eq. 2 right; Eq. 3; prior art: Alg. 2).  Four kernels with the same result:
 //
 //  pull (owner computes, A^T stored as CSC): one wavefront owns a run of the
 //    in-entries of destination node j; lane t keeps sp_index[j,t] and a running
@@ -33,6 +33,8 @@
 //    (slab, destination) visits and adds the visit's in-entries to the
 //    destination's dXs row (read-modify-write, the row is revisited once per
 //    slab).  Pays off when a visit has several entries, i.e. dense neighbourhoods.
+//    Two forms: the sampled gather (small k), and from k >= dim/8 a form that adds
+//    up whole dY rows in registers and samples the sum once per visit.
 //
 // This header holds the kernel templates that read dY; one translation unit per storage format of dY
 // (fp32, bf16, fp16: the 16-bit formats are widened exactly, products and sums are fp32 throughout)
