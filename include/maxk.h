@@ -164,6 +164,8 @@ MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void
  * lines of dY rows, so the row length in bytes is what the kernel's time follows.  Values are widened exactly;
  * products and sums are fp32 and d_dXs is fp32, so the result meets the bound of maxk_sspmm_bwd against the
  * definition evaluated on the 16-bit values.  Rounding fp32 gradients to 16 bits is the caller's decision.
+ * The slab-pull kernel regroups A^T per slab height, and 16-bit rows use a height of their own: that table is
+ * built (allocated) by the first call that needs it, not by maxk_graph_reserve.
  */
 MAXK_API maxk_status maxk_sspmm_bwd_narrow(maxk_graph* g, const void* d_dY, int32_t value_type, const void* d_sp_index,
                                            int32_t index_bytes, int32_t dim, int32_t k, float* d_dXs, void* stream);
