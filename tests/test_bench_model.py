@@ -22,6 +22,10 @@ def test_traffic_model_closed_forms():
     assert b["bwd"] == 4 * (N + 1) + 8 * nnz + 4 * k * nnz + N * k * 5
     assert b["topk"] == 4 * N * dim + 5 * N * k
     assert b["spmm"] == 4 * (N + 1) + 8 * nnz + 4 * nnz * dim + 4 * N * dim
+    # 16-bit CBSR values: 2 + ib bytes per kept position instead of 4 + ib; nothing else changes
+    h = algorithmic_bytes(N, nnz, dim, k, index_bytes=1, value_bytes=2)
+    assert h["fwd_cbsr_reads"] == 3 * k * nnz and b["fwd"] - h["fwd"] == 2 * k * nnz
+    assert h["bwd"] == b["bwd"] and h["spmm"] == b["spmm"]
 
 
 def test_headline_times_at_peak_bandwidth():
