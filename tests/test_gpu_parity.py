@@ -406,3 +406,31 @@ def test_graph_create_rejects_bad_structure():
     want = np.array([[0 + 8, 1 + 9, 2 + 10, 3 + 11], [4, 5, 6, 7], [0 + 4, 1 + 5, 2 + 6, 3 + 7]], np.float32)
     assert np.array_equal(Y.cpu().numpy(), want)
     g2.destroy()
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_shapes_sweep(seed):
+    """Seeded random (N, density, dim, k, index width) cases through every kernel: catches the shape-dependent paths
+    (vector widths, register layouts, packed records, both slab-pull forms, tails) the fixed lists may miss."""
+    rng = np.random.default_rng(seed)
+    for case in range(16):
+        N = int(rng.integers(1, 2500))
+        dim = int(rng.choice([4, 8, 20, 64, 100, 128, 256, 260, 384, 512, 768, 1024, int(rng.integers(1, 1025))]))
+        k = int(rng.integers(1, dim + 1))
+        if rng.random() < 0.3:
+            k = max(1, dim // int(rng.choice([2, 4, 8, 16])))
+        ib = 1 if dim <= 256 and rng.random() < 0.5 else (2 if rng.random() < 0.7 else 4)
+        avg_deg = float(rng.choice([0.5, 2, 8, 40, 150]))
+        directed = bool(rng.random() < 0.7)
+        M = int(min(0.4 * N * (N - 1) if N > 1 else 0, max(0, N * avg_deg)))
+        if not directed:
+            M //= 2
+        say(f"  case {case}: N={N} M={M} dim={dim} k={k} ib={ib} directed={directed}")
+        g = synth.make_graph(N, M, 0, directed=directed, self_loops=bool(rng.random() < 0.5), seed=1000 * seed + case,
+                             weights="normal")
+        dg = DeviceGraph(g)
+        H, dY = synth.normal_matrix(g.N, dim, 7000 + case), synth.normal_matrix(g.N, dim, 8000 + case)
+        if rng.random() < 0.3:
+            synth.add_tie_rows(H, seed=case, percent=30, pool=8, const_every=4)
+        full_pass(dg, H, dY, k, ib, sampled=False, spmm=bool(rng.random() < 0.3))
+        dg.close()
