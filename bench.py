@@ -235,7 +235,8 @@ def main() -> int:
                         "bwd_ms": round(tb, 4), "bwd_edges_k_per_s": nnz * k / (tb * 1e-3),
                         "bwd_hbm_frac": round(b["bwd"] / (tb * 1e-3) / 8e12, 4),
                         "bwd_speedup_vs_spmm": round(spmm_ms / tb, 2),
-                        "fwd_bwd_edges_k_per_s": 2.0 * nnz * k / ((tf + tb) * 1e-3)})
+                        "fwd_bwd_edges_k_per_s": 2.0 * nnz * k / ((tf + tb) * 1e-3),
+                        "fwd_bwd_hbm_frac": round((b["fwd"] + b["bwd"]) / ((tf + tb) * 1e-3) / 8e12, 4)})
             per_k.append(row)
             del sd, si, dx
 
@@ -281,7 +282,8 @@ def main() -> int:
                               "sspmm_bwd": round(t_bwd, 4)},
         "hbm_frac_by_algorithmic_bytes": {"fwd": round(ab["fwd"] / (t_fwd * 1e-3) / 8e12, 4),
                                           "bwd": round(ab["bwd"] / (t_bwd * 1e-3) / 8e12, 4),
-                                          "topk": round(ab["topk"] / (t_topk * 1e-3) / 8e12, 4)},
+                                          "topk": round(ab["topk"] / (t_topk * 1e-3) / 8e12, 4),
+                                          "fwd+bwd": round((ab["fwd"] + ab["bwd"]) / ((t_fwd + t_bwd) * 1e-3) / 8e12, 4)},
         "spmm_baseline_ms": None if spmm_ms is None else round(spmm_ms, 4),
         "per_k": per_k,
         "roofline": roofline,
