@@ -17,16 +17,14 @@
  *   - Outputs are OVERWRITTEN; the caller need not clear them.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work and return; they do not synchronise the device.
- *     The compute calls allocate nothing (per-graph workspaces are made by
- *     maxk_graph_create / maxk_graph_reserve), with one exception stated at
- *     maxk_graph_reserve.
+ *     After maxk_graph_reserve* the compute calls allocate nothing (see there).
  *   - Return value: MAXK_OK (0) or a negative maxk_status.  Nothing throws,
  *     aborts or prints.  N == 0 is a valid no-op.  Array CONTENTS are not
  *     validated by the compute calls (NaN in H, column ids outside [0,N) and
  *     sp_index outside [0,dim) are contract violations).
  *   - Calls on one maxk_graph must not overlap in time (they share its workspace).
- *   - Tuning knobs read from the environment (results never depend on them): MAXK_CHUNK (entries per
- *     work item, default 2048, read by maxk_graph_create), MAXK_SLAB_KB (KiB of dY per slab of the slab-pull
+ *   - Tuning knobs, read from the environment once per handle by maxk_graph_create (results never depend on
+ *     them): MAXK_CHUNK (entries per work item, default 2048), MAXK_SLAB_KB (KiB of dY per slab of the slab-pull
  *     backward kernel, default 3584), MAXK_FWD_PACK_MAX (largest CBSR row in bytes that the forward pass
  *     repacks into one record per node, default 96).
  */
@@ -64,8 +62,12 @@ enum {
     MAXK_BWD_PUSH_CSR = 2,/* Alg. 2's dataflow: stage dY[i,:] on chip, push along row i of A with fp32 atomics */
     MAXK_BWD_EXPAND_REDUCE = 3,/* Alg. 2's staging without atomics: write each entry's k products to a per-graph
                                   buffer (nnz*k floats, sequential), then sum them per destination node */
-    MAXK_BWD_SLAB_PULL = 4    /* owner-computes pull, tiled so the dY rows being gathered stay in L2: source rows are
+    MAXK_BWD_SLAB_PULL = 4,   /* owner-computes pull, tiled so the dY rows being gathered stay in L2: source rows are
                                   swept slab by slab, one launch per slab; deterministic, no atomics */
+    MAXK_BWD_TILED = 5        /* Alg. 2's on-chip staging of dY rows, turned round: a workgroup keeps the dXs rows of a
+                                  set of destination nodes in LDS and streams tiles of dY rows through LDS, so a dY row
+                                  is fetched once per destination set instead of once per entry.  fp32 dY, k % 4 == 0,
+                                  dim % 4 == 0, dim <= 512, 16-byte aligned dY; other calls run MAXK_BWD_SLAB_PULL */
 };
 
 /* Storage format of the CBSR values for the *_narrow entry points: fp32, or a 16-bit pattern in a uint16_t. */
@@ -94,13 +96,19 @@ MAXK_API maxk_status maxk_graph_create(maxk_graph** out, int64_t N, int64_t nnz,
 MAXK_API maxk_status maxk_graph_destroy(maxk_graph* g);
 
 /*
- * Pre-allocates the handle's workspaces (partial sums of split rows; the nnz*k
- * float buffer of the expand/reduce backward kernel when that kernel would be
- * used) for hidden width `dim` and MaxK `k`, so that later compute calls with
- * dim' <= dim, k' <= k allocate nothing.  Without it, the first compute call needing a larger workspace grows
- * it (one synchronous allocation), later ones reuse it.
+ * Builds everything the handle's compute calls need for hidden width `dim`, MaxK `k` and (for the backward pass)
+ * dY stored as `dy_value_type`: the partial-sum workspace of split rows, the forward pass's repack buffer, and
+ * what the backward kernel that would run needs (the nnz*k float buffer of expand/reduce, the slab regrouping
+ * of A^T for the slab height of (dim, dy_value_type), the visit lists of the LDS-tiled kernel for (dim, k)).
+ * After it, compute calls with the same dim and k (forward, SpMM: any dim' <= dim, k' <= k) allocate nothing,
+ * do not synchronise and read no environment variable.  Tables are cached per shape for the life of the handle,
+ * so alternating several (dim, k) or dY formats never rebuilds one.  Without a reserve, the first compute call that
+ * needs a table or a larger workspace builds it (synchronous allocations; the tables also sort A^T), later ones
+ * reuse it; the same holds for a backward call whose pointers turn out too misaligned for the reserved kernel.
+ * Synchronises the device.  maxk_graph_reserve is the fp32-dY form.
  */
 MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k);
+MAXK_API maxk_status maxk_graph_reserve_narrow(maxk_graph* g, int32_t dim, int32_t k, int32_t dy_value_type);
 
 /* Selects the backward kernel (MAXK_BWD_*). */
 MAXK_API maxk_status maxk_graph_set_bwd_mode(maxk_graph* g, int32_t mode);
@@ -164,8 +172,8 @@ MAXK_API maxk_status maxk_sspmm_bwd(maxk_graph* g, const float* d_dY, const void
  * lines of dY rows, so the row length in bytes is what the kernel's time follows.  Values are widened exactly;
  * products and sums are fp32 and d_dXs is fp32, so the result meets the bound of maxk_sspmm_bwd against the
  * definition evaluated on the 16-bit values.  Rounding fp32 gradients to 16 bits is the caller's decision.
- * The slab-pull kernel regroups A^T per slab height, and 16-bit rows use a height of their own: that table is
- * built (allocated) by the first call that needs it, not by maxk_graph_reserve.
+ * The slab-pull kernel regroups A^T per slab height, and 16-bit rows use a height of their own
+ * (maxk_graph_reserve_narrow builds it ahead of time).
  */
 MAXK_API maxk_status maxk_sspmm_bwd_narrow(maxk_graph* g, const void* d_dY, int32_t value_type, const void* d_sp_index,
                                            int32_t index_bytes, int32_t dim, int32_t k, float* d_dXs, void* stream);
@@ -189,11 +197,6 @@ MAXK_API const char* maxk_status_string(maxk_status s);
 
 /* hipError_t (as int) of the last HIP failure seen by this thread, 0 if none. */
 MAXK_API int32_t maxk_last_hip_error(void);
-
-/* Host-side introspection for tests: the number of private output-row copies the forward kernel keeps in
- * LDS for MaxK k (entries that share one 64-lane instruction must map to different copies), or a negative
- * maxk_status for k < 1. */
-MAXK_API int32_t maxk_fwd_private_copies(int32_t k);
 
 /* Library version, MAJOR*10000 + MINOR*100 + PATCH. */
 MAXK_API int32_t maxk_version(void);

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     BWD_PULL_CSC,
     BWD_PUSH_CSR,
     BWD_SLAB_PULL,
+    BWD_TILED,
     VALUE_BF16,
     VALUE_F16,
     VALUE_F32,

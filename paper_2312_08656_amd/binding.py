@@ -10,11 +10,12 @@ import torch
 _HERE = Path(__file__).resolve().parent
 _LIB: Optional[ctypes.CDLL] = None
 
-BWD_AUTO, BWD_PULL_CSC, BWD_PUSH_CSR, BWD_EXPAND_REDUCE, BWD_SLAB_PULL = 0, 1, 2, 3, 4
+BWD_AUTO, BWD_PULL_CSC, BWD_PUSH_CSR, BWD_EXPAND_REDUCE, BWD_SLAB_PULL, BWD_TILED = 0, 1, 2, 3, 4, 5
 VALUE_F32, VALUE_BF16, VALUE_F16 = 0, 1, 2
 
 EXPORTS = (
-    "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode", "maxk_graph_bwd_choice",
+    "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_reserve_narrow",
+    "maxk_graph_set_bwd_mode", "maxk_graph_bwd_choice",
     "maxk_graph_info",
     "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_topk_cbsr_narrow", "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd",
     "maxk_sspmm_bwd_narrow", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
@@ -43,6 +44,7 @@ def load_library() -> ctypes.CDLL:
     lib.maxk_graph_create.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, vp, vp]
     lib.maxk_graph_destroy.argtypes = [vp]
     lib.maxk_graph_reserve.argtypes = [vp, i32, i32]
+    lib.maxk_graph_reserve_narrow.argtypes = [vp, i32, i32, i32]
     lib.maxk_graph_set_bwd_mode.argtypes = [vp, i32]
     lib.maxk_graph_bwd_choice.argtypes = [vp, i32, i32]
     lib.maxk_graph_bwd_choice.restype = i32
@@ -55,7 +57,8 @@ def load_library() -> ctypes.CDLL:
     lib.maxk_sspmm_bwd_narrow.argtypes = [vp, vp, i32, vp, i32, i32, i32, vp, vp]
     lib.maxk_cbsr_scatter.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp]
     lib.spmm_baseline.argtypes = [vp, vp, i32, vp, vp]
-    for name in ("maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_set_bwd_mode",
+    for name in ("maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_reserve_narrow",
+                 "maxk_graph_set_bwd_mode",
                  "maxk_graph_info", "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_topk_cbsr_narrow",
                  "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd", "maxk_sspmm_bwd_narrow", "maxk_cbsr_scatter",
                  "spmm_baseline",
@@ -116,8 +119,11 @@ class MaxKGraph:
             raise MaxKError("graph handle already destroyed")
         return self._h
 
-    def reserve(self, dim: int, k: int) -> None:
-        _check(load_library().maxk_graph_reserve(self.handle, dim, k), "maxk_graph_reserve")
+    def reserve(self, dim: int, k: int, dy_dtype=torch.float32) -> None:
+        """Builds every workspace and table that compute calls with (dim' <= dim, k' <= k; backward: this dim, k and
+        dY dtype) need, so that they allocate nothing."""
+        _check(load_library().maxk_graph_reserve_narrow(self.handle, dim, k, _VALUE_TYPE[dy_dtype]),
+               "maxk_graph_reserve_narrow")
 
     def set_bwd_mode(self, mode: int) -> None:
         _check(load_library().maxk_graph_set_bwd_mode(self.handle, mode), "maxk_graph_set_bwd_mode")
@@ -128,7 +134,7 @@ class MaxKGraph:
         if c < 0:
             _check(c, "maxk_graph_bwd_choice")
         return {BWD_PULL_CSC: "pull", BWD_PUSH_CSR: "push", BWD_EXPAND_REDUCE: "expand_reduce",
-                BWD_SLAB_PULL: "slab_pull"}[c]
+                BWD_SLAB_PULL: "slab_pull", BWD_TILED: "tiled"}[c]
 
     def info(self) -> dict:
         vals = [ctypes.c_int64() for _ in range(6)]

@@ -11,7 +11,7 @@ HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libmaxk.so"
 SOURCES = ["graph.hip", "topk.hip", "spgemm_fwd.hip", "spgemm_fwd_f32.hip", "spgemm_fwd_bf16.hip", "spgemm_fwd_f16.hip",
-           "sspmm_bwd.hip", "sspmm_bwd_f32.hip", "sspmm_bwd_bf16.hip", "sspmm_bwd_f16.hip", "spmm.hip"]
+           "sspmm_bwd.hip", "sspmm_bwd_f32.hip", "sspmm_bwd_bf16.hip", "sspmm_bwd_f16.hip", "sspmm_bwd_tiled.hip", "spmm.hip"]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions from float code
 HIPCC_FLAGS = [

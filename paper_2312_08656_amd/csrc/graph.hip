@@ -36,13 +36,15 @@ struct maxk_graph {
     int64_t partial_floats = 0;
     float* d_expand = nullptr;  // per-entry contributions of the expand/reduce backward kernel (nnz * k floats)
     int64_t expand_floats = 0;
-    maxk::SlabSet slabs;        // built on demand for one slab height at a time (fp32 dY)
-    maxk::SlabSet slabs16;      // the same for 16-bit dY, whose rows are half as long
+    std::vector<maxk::SlabSet*> slab_cache;    // A^T regrouped per slab height (one per height ever asked for)
+    std::vector<maxk::TiledSet*> tiled_cache;  // visit lists of the LDS-tiled kernel, one per (set size, k / 4)
     char* d_packed = nullptr;   // forward kernel's per-call repack of a small-k CBSR (one record per node)
     int64_t packed_bytes = 0;
     int64_t max_degree = 0;
     int32_t bwd_mode = MAXK_BWD_AUTO;
-    int32_t chunk = 0;
+    int32_t chunk = 0;         // tuning knobs, read from the environment once, by maxk_graph_create
+    int32_t slab_kb = 0;
+    int32_t fwd_pack_max = 0;
     int device = 0;
 };
 
@@ -321,12 +323,10 @@ __global__ __launch_bounds__(256) void fill_i64_kernel(int64_t* __restrict__ p, 
     if (i < n) p[i] = value;
 }
 
-// Regroups A^T by slabs of `slab_rows` source rows (see SlabSet).  Synchronises the device.
+// Regroups A^T by slabs of `slab_rows` source rows (see SlabSet) into the empty set S.  Synchronises the device.
 maxk_status build_slabs(maxk_graph* g, SlabSet& S, int32_t slab_rows)
 {
-    if (S.slab_rows == slab_rows) return MAXK_OK;
     MAXK_HIP_TRY(hipDeviceSynchronize());
-    free_slabs(S);
     const int64_t N = g->N, nnz = g->nnz;
     const int32_t n_slabs = (int32_t)((N + slab_rows - 1) / slab_rows);
     S.h_slab_visit = (int64_t*)std::calloc((size_t)n_slabs + 1, sizeof(int64_t));
@@ -434,17 +434,46 @@ maxk_status build_slabs(maxk_graph* g, SlabSet& S, int32_t slab_rows)
 }
 
 // Slab height for hidden width `dim`: a slab of dY should sit comfortably inside one XCD's 4 MB L2.
-int32_t slab_rows_for(int dim, int val_bytes = 4)
+int32_t slab_rows_for(const maxk_graph* g, int dim, int val_bytes = 4)
 {
-    const int kb = env_int("MAXK_SLAB_KB", 3584, 64, 1 << 20);
-    const int64_t rows = (int64_t)kb * 1024 / ((int64_t)dim * val_bytes);
+    const int64_t rows = (int64_t)g->slab_kb * 1024 / ((int64_t)dim * val_bytes);
     return (int32_t)std::max<int64_t>(rows, 64);
 }
 
-// The forward kernel repacks the CBSR when a row of it is well below a cache line.
-bool fwd_uses_packed(int k, int index_bytes, int val_bytes)
+// The regrouping of A^T for one slab height: built on first use (or by maxk_graph_reserve*), then kept until the
+// handle is destroyed, so alternating hidden widths or dY formats on one handle never rebuilds anything.
+maxk_status slabs_for(maxk_graph* g, int32_t slab_rows, SlabSet** out)
 {
-    return k * (val_bytes + index_bytes) <= env_int("MAXK_FWD_PACK_MAX", 96, 0, 1 << 20);
+    for (SlabSet* S : g->slab_cache)
+        if (S->slab_rows == slab_rows) { *out = S; return MAXK_OK; }
+    SlabSet* S = new (std::nothrow) SlabSet();
+    if (!S) return MAXK_OUT_OF_MEMORY;
+    const maxk_status st = build_slabs(g, *S, slab_rows);
+    if (st != MAXK_OK) { delete S; return st; }
+    try { g->slab_cache.push_back(S); } catch (const std::bad_alloc&) { free_slabs(*S); delete S; return MAXK_OUT_OF_MEMORY; }
+    *out = S;
+    return MAXK_OK;
+}
+
+maxk_status tiled_for(maxk_graph* g, int dim, int k, TiledSet** out)
+{
+    int D = 0, n_dsets = 0;
+    if (!tiled_shape(g->N, dim, k, D, n_dsets)) return MAXK_UNSUPPORTED;
+    for (TiledSet* T : g->tiled_cache)
+        if (T->D == D && T->LPV == k / tiled_positions_per_lane(k)) { *out = T; return MAXK_OK; }
+    TiledSet* T = new (std::nothrow) TiledSet();
+    if (!T) return MAXK_OUT_OF_MEMORY;
+    const maxk_status st = build_tiled(*T, g->N, g->nnz, g->d_csc_ptr, g->d_csc_src, g->d_csc_val, D, k);
+    if (st != MAXK_OK) { delete T; return st; }
+    try { g->tiled_cache.push_back(T); } catch (const std::bad_alloc&) { free_tiled(*T); delete T; return MAXK_OUT_OF_MEMORY; }
+    *out = T;
+    return MAXK_OK;
+}
+
+// The forward kernel repacks the CBSR when a row of it is well below a cache line.
+bool fwd_uses_packed(const maxk_graph* g, int k, int index_bytes, int val_bytes)
+{
+    return k * (val_bytes + index_bytes) <= g->fwd_pack_max;
 }
 
 maxk_status ensure_packed(maxk_graph* g, int k, int index_bytes, int val_bytes)
@@ -482,9 +511,17 @@ maxk_status ensure_expand(maxk_graph* g, int k)
 // (slab, destination) visit, so it needs several in-entries per visit: dense neighbourhoods.
 // Otherwise: expand/reduce moves 8k bytes per stored entry through HBM, plain pull touches about
 // min(k, dim/32) cache lines of a dY row per entry whatever k is, so pull wins once k is large.
-int auto_bwd_mode(const maxk_graph* g, int dim, int k, int val_bytes = 4)
+int auto_bwd_mode(const maxk_graph* g, int dim, int k, int val_bytes = 4, bool tiled_ok = true)
 {
-    const double n_slabs = std::ceil((double)g->N / slab_rows_for(dim, val_bytes));
+    // LDS-tiled: a workgroup's wavefront gets nnz * 16 * D / (4 N^2) visits per tile; it pays off once those fill
+    // a good part of a wave instruction (64 / (k/4) visits)
+    int D = 0, n_dsets = 0;
+    if (tiled_ok && val_bytes == 4 && g->nnz > 0 && tiled_shape(g->N, dim, k, D, n_dsets)) {
+        const double per_list = (double)g->nnz * 16.0 * D / (4.0 * (double)g->N * (double)g->N);
+        const double n_lists = (double)n_dsets * 4.0 * std::ceil((double)g->N / 16.0);
+        if (per_list >= 0.4 * (64.0 / (k / tiled_positions_per_lane(k))) && n_lists < 2.6e8) return MAXK_BWD_TILED;
+    }
+    const double n_slabs = std::ceil((double)g->N / slab_rows_for(g, dim, val_bytes));
     const double entries_per_visit = (double)g->nnz / std::max(1.0, (double)g->N * n_slabs);
     if (entries_per_visit >= 2.0 && n_slabs * (double)g->N < 1.8e19) return MAXK_BWD_SLAB_PULL;
     // expected cache lines of a dY row touched by k sorted columns; measured crossover on four graphs:
@@ -529,6 +566,8 @@ MAXK_API maxk_status maxk_graph_create(maxk_graph** out, int64_t N, int64_t nnz,
     g->d_col = d_colidx;
     g->d_val = d_val;
     g->chunk = env_int("MAXK_CHUNK", 2048, 64, 1 << 20);  // measured plateau: 2048 and up
+    g->slab_kb = env_int("MAXK_SLAB_KB", 3584, 64, 1 << 20);
+    g->fwd_pack_max = env_int("MAXK_FWD_PACK_MAX", 96, 0, 1 << 20);
     (void)hipGetDevice(&g->device);
 
     maxk_status st = MAXK_OK;
@@ -579,38 +618,55 @@ MAXK_API maxk_status maxk_graph_destroy(maxk_graph* g)
     (void)hipFree(g->d_csc_entry);
     (void)hipFree(g->d_expand);
     (void)hipFree(g->d_packed);
-    free_slabs(g->slabs);
-    free_slabs(g->slabs16);
+    for (SlabSet* S : g->slab_cache) { free_slabs(*S); delete S; }
+    for (TiledSet* T : g->tiled_cache) { free_tiled(*T); delete T; }
     (void)hipFree(g->d_partials);
     delete g;
     return MAXK_OK;
 }
 
-MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k)
+MAXK_API maxk_status maxk_graph_reserve_narrow(maxk_graph* g, int32_t dim, int32_t k, int32_t dy_value_type)
 {
     if (!g || dim < 1 || k < 1 || k > dim) return MAXK_INVALID_ARGUMENT;
+    if (dy_value_type < MAXK_VALUE_F32 || dy_value_type > MAXK_VALUE_F16) return MAXK_INVALID_ARGUMENT;
     if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
+    if (g->N == 0) return MAXK_OK;
     maxk_status st = ensure_workspace(g, dim, k);
     if (st != MAXK_OK) return st;
     for (int vb = 2; vb <= 4; vb += 2) {
         for (int ib = 1; ib <= 4; ib *= 2) {
             for (int kk = 1; kk <= k; ++kk) {  // the largest repacked record among k' <= k
-                if (!fwd_uses_packed(kk, ib, vb)) break;
-                if (kk == k || !fwd_uses_packed(kk + 1, ib, vb)) {
+                if (!fwd_uses_packed(g, kk, ib, vb)) break;
+                if (kk == k || !fwd_uses_packed(g, kk + 1, ib, vb)) {
                     st = ensure_packed(g, kk, ib, vb);
                     if (st != MAXK_OK) return st;
                 }
             }
         }
     }
-    const int mode = g->bwd_mode == MAXK_BWD_AUTO ? auto_bwd_mode(g, dim, k) : g->bwd_mode;
-    if (mode == MAXK_BWD_SLAB_PULL) return build_slabs(g, g->slabs, slab_rows_for(dim));
+    const int vb = value_bytes(dy_value_type);
+    const int mode = g->bwd_mode == MAXK_BWD_AUTO ? auto_bwd_mode(g, dim, k, vb) : g->bwd_mode;
+    if (mode == MAXK_BWD_TILED) {
+        TiledSet* T = nullptr;
+        st = tiled_for(g, dim, k, &T);
+        if (st != MAXK_UNSUPPORTED) return st;
+        // the compute call falls back to the slab kernel for shapes the tiled one does not take
+    }
+    if (mode == MAXK_BWD_SLAB_PULL || mode == MAXK_BWD_TILED) {
+        SlabSet* S = nullptr;
+        return g->nnz ? slabs_for(g, slab_rows_for(g, dim, vb), &S) : MAXK_OK;
+    }
     return mode == MAXK_BWD_EXPAND_REDUCE ? ensure_expand(g, k) : MAXK_OK;
+}
+
+MAXK_API maxk_status maxk_graph_reserve(maxk_graph* g, int32_t dim, int32_t k)
+{
+    return maxk_graph_reserve_narrow(g, dim, k, MAXK_VALUE_F32);
 }
 
 MAXK_API maxk_status maxk_graph_set_bwd_mode(maxk_graph* g, int32_t mode)
 {
-    if (!g || mode < MAXK_BWD_AUTO || mode > MAXK_BWD_SLAB_PULL) return MAXK_INVALID_ARGUMENT;
+    if (!g || mode < MAXK_BWD_AUTO || mode > MAXK_BWD_TILED) return MAXK_INVALID_ARGUMENT;
     g->bwd_mode = mode;
     return MAXK_OK;
 }
@@ -671,7 +727,7 @@ MAXK_API maxk_status maxk_spgemm_fwd_narrow(maxk_graph* g, const void* d_sp_data
     maxk_status st = ensure_workspace(g, dim, k);
     if (st != MAXK_OK) return st;
     char* packed = nullptr;
-    if (fwd_uses_packed(k, index_bytes, vb)) {
+    if (fwd_uses_packed(g, k, index_bytes, vb)) {
         st = ensure_packed(g, k, index_bytes, vb);
         if (st != MAXK_OK) return st;
         packed = g->d_packed;
@@ -700,12 +756,22 @@ MAXK_API maxk_status maxk_sspmm_bwd_narrow(maxk_graph* g, const void* d_dY, int3
     maxk_status st = ensure_workspace(g, dim, k);
     if (st != MAXK_OK) return st;
     int mode = g->bwd_mode;
-    if (mode == MAXK_BWD_AUTO) mode = auto_bwd_mode(g, dim, k, vb);
+    const bool tiled_ok = tiled_supports(d_dY, value_type, d_sp_index, index_bytes, dim, k);
+    if (mode == MAXK_BWD_AUTO) mode = auto_bwd_mode(g, dim, k, vb, tiled_ok);
+    if (g->nnz == 0) return launch_fill_zero(d_dXs, g->N * (int64_t)k, (hipStream_t)stream);
+    if (mode == MAXK_BWD_TILED) {
+        TiledSet* T = nullptr;
+        st = tiled_ok ? tiled_for(g, dim, k, &T) : MAXK_UNSUPPORTED;
+        if (st == MAXK_OK)
+            return launch_bwd_tiled(*T, d_dY, value_type, d_sp_index, index_bytes, g->N, dim, k, d_dXs, (hipStream_t)stream);
+        if (st != MAXK_UNSUPPORTED) return st;
+        mode = MAXK_BWD_SLAB_PULL;  // shapes, formats and alignments the tiled kernel does not take
+    }
     if (mode == MAXK_BWD_SLAB_PULL) {
-        SlabSet& S = vb == 4 ? g->slabs : g->slabs16;
-        st = build_slabs(g, S, slab_rows_for(dim, vb));
+        SlabSet* S = nullptr;
+        st = slabs_for(g, slab_rows_for(g, dim, vb), &S);
         if (st != MAXK_OK) return st;
-        return launch_bwd_slab_pull(S, d_dY, value_type, d_sp_index, index_bytes, g->N, dim, k, d_dXs, (hipStream_t)stream);
+        return launch_bwd_slab_pull(*S, d_dY, value_type, d_sp_index, index_bytes, g->N, dim, k, d_dXs, (hipStream_t)stream);
     }
     if (mode == MAXK_BWD_EXPAND_REDUCE) {
         st = ensure_expand(g, k);

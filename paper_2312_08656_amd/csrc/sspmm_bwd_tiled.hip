@@ -1,0 +1,735 @@
+// Backward aggregation, LDS-tiled form (Eq. 2 right; Eq. 3; prior art: Alg. 2's staging of a dY row on chip).
+//
+// Every other backward kernel here fetches, per stored entry, the cache lines of a dY row that the destination's k
+// columns fall into: about 1 KB of 128-byte lines per entry at hidden width 256 for 4k useful bytes, and the L2 -> L1
+// path (64 bytes per clock per CU) is what they wait for.  This kernel turns the traffic round: a workgroup OWNS a set
+// of D destination nodes, keeps their D x k accumulators in LDS for its whole life, and streams the source rows of dY
+// through LDS in tiles of 16 rows with full, coalesced 16-byte loads.  A tile is used by every entry (i -> j) with i in
+// the tile and j in the set, so a row of dY is fetched once per destination set instead of once per entry:
+// (N / D) * N * dim * 4 bytes in all.  The sampled reads dY[i, sp_index[j, t]] and the read-add-write of the accumulators
+// are LDS traffic.  All workgroups of an XCD sweep the same source range at the same time, so the rows come from that
+// XCD's L2.
+//
+// Work assignment inside a workgroup (9 wavefronts):
+//   - wavefronts 4..7 only load: each keeps a register queue of the next tiles' rows (plain 16-byte loads, several
+//     tiles ahead: the queue depth is what hides the L2 latency) and writes one tile per step into one of two LDS row
+//     buffers;
+//   - wavefronts 0..3 only accumulate.  A "visit" is one (tile, destination) pair with at least one entry; k/4 lanes
+//     work on it, four CBSR positions each, so a wave instruction covers a "set" of 64/(k/4) visits.  The visits of a
+//     tile have distinct destinations, so the sets of one tile can be worked on by different wavefronts at the same
+//     time without two lanes ever touching one accumulator; set s of the workgroup's list goes to wavefront s % 4.
+//     A visit's first entry sits in the visit record, a second one in a parallel array, further ones (rare) in a chain;
+//   - wavefront 8 touches cache lines of the tiles further ahead so that they are in L2 when the loaders ask.
+//   One workgroup barrier per tile hands a row buffer from the loaders to the accumulators and orders the
+//   accumulator updates of consecutive tiles.
+//
+// The visit lists are built once per (D, k/4) by sorting the entries of A^T by (destination set, tile, destination,
+// source); every tile's list is padded to a multiple of four sets, so that each accumulating wavefront walks an
+// arithmetic progression of sets and can fetch its records far ahead without looking at the directory.
+#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+
+#include <rocprim/rocprim.hpp>
+
+#include "common.hpp"
+
+namespace maxk {
+namespace {
+
+constexpr int kTileRows = 16;       // source rows per tile
+constexpr int kAccWaves = 8;        // accumulating wavefronts
+constexpr int kLoadWaves = 4;       // loading wavefronts
+constexpr int kTiledThreads = (kAccWaves + kLoadWaves + 1) * kWave;  // + one wavefront that prefetches
+constexpr int kLdsBytes = 160 * 1024;
+constexpr int kRowQueue = 4;        // tiles a loading wavefront keeps in flight
+constexpr int kRecAhead = 8;        // sets between the fetch of a visit record and its use
+constexpr int kIdxAhead = 4;        // sets between the fetch of a visit's CBSR columns and their use
+constexpr int kPrefetchAhead = 32;  // tiles between the L2 prefetch and the loads that use it
+constexpr int kPrefetchGroup = 16;  // tiles covered by one round of prefetch instructions
+
+// second word of a visit record: accumulator row (in units of four floats), source row within the tile, flags
+constexpr uint32_t kVisitAccMask = 0x3FFFu;
+constexpr uint32_t kVisitSrcShift = 14;                  // 6 bits
+constexpr uint32_t kVisitHasExtra = 1u << 20;
+constexpr uint32_t kVisitNull = 1u << 21;                // padding slot
+// second word of an extra entry: source row within the tile, chain position of the next one, "another one follows"
+constexpr uint32_t kExtraMore = 1u << 31;
+constexpr uint32_t kExtraNextShift = 6;                  // 25 bits
+constexpr int64_t kMaxChain = (int64_t)1 << 25;
+
+// ------------------------------------------------------------------ table build ----
+
+// key = ((set * n_tiles + tile) << 18) | dest_local << 6 | src_local, one per in-entry of A^T
+__global__ __launch_bounds__(256) void tiled_keys_kernel(const int32_t* __restrict__ csc_ptr,
+                                                         const int32_t* __restrict__ csc_src, int64_t N, int64_t nnz,
+                                                         int32_t D, int32_t n_tiles, uint64_t* __restrict__ key)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
+        int64_t lo = 0, hi = N;  // largest j with csc_ptr[j] <= p
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if ((int64_t)csc_ptr[mid] <= p) lo = mid; else hi = mid;
+        }
+        const int32_t j = (int32_t)lo, i = csc_src[p];
+        const int32_t d = j / D, jl = j - d * D;
+        const int32_t tile = i / kTileRows, il = i - tile * kTileRows;
+        const uint64_t group = (uint64_t)d * (uint64_t)n_tiles + (uint64_t)tile;
+        key[p] = (group << 18) | ((uint64_t)jl << 6) | (uint64_t)il;
+    }
+}
+
+// head[p] = entry p opens a visit; third[p] = entry p is the third or a later one of its visit
+__global__ __launch_bounds__(256) void tiled_flags_kernel(const uint64_t* __restrict__ key, int64_t nnz,
+                                                          uint32_t* __restrict__ head, uint32_t* __restrict__ third)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
+        const uint64_t v = key[p] >> 6;
+        const bool h = p == 0 || (key[p - 1] >> 6) != v;
+        const bool h1 = p < 2 ? true : ((key[p - 2] >> 6) != v);  // p-1 opens the visit or belongs to another one
+        head[p] = h ? 1u : 0u;
+        third[p] = (!h && !h1) ? 1u : 0u;
+    }
+}
+
+// sets[g] = wave instructions that the visits of group g need; first_visit[g] = visits before group g
+__global__ __launch_bounds__(256) void tiled_groups_kernel(const uint64_t* __restrict__ key,
+                                                           const uint32_t* __restrict__ rank, int64_t nnz,
+                                                           int64_t n_groups, int32_t E, uint32_t n_visits,
+                                                           uint32_t* __restrict__ first_visit,
+                                                           uint32_t* __restrict__ sets)
+{
+    const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g > n_groups) return;
+    auto lower = [&](uint64_t bound) {  // first entry whose key is >= bound
+        int64_t lo = 0, hi = nnz;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (key[mid] < bound) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+    };
+    auto visits_before = [&](int64_t pos) { return pos < nnz ? rank[pos] - 1u : n_visits; };
+    const uint32_t fv = visits_before(lower((uint64_t)g << 18));
+    first_visit[g] = fv;
+    if (g < n_groups) {
+        const uint32_t nv = visits_before(lower((uint64_t)(g + 1) << 18)) - fv;
+        sets[g] = (nv + (uint32_t)E - 1u) / (uint32_t)E;
+    } else {
+        sets[g] = 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void tiled_fill_null_kernel(uint2* __restrict__ rec, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) rec[i] = make_uint2(0u, kVisitNull);
+}
+
+__global__ __launch_bounds__(256) void tiled_records_kernel(const uint64_t* __restrict__ key,
+                                                            const float* __restrict__ val,
+                                                            const uint32_t* __restrict__ head,
+                                                            const uint32_t* __restrict__ rank,
+                                                            const uint32_t* __restrict__ third,
+                                                            const uint32_t* __restrict__ chain_pos, int64_t nnz,
+                                                            int32_t E, int32_t LPV,
+                                                            const uint32_t* __restrict__ first_visit,
+                                                            const uint32_t* __restrict__ dir_sets,
+                                                            uint2* __restrict__ rec, uint2* __restrict__ extra1,
+                                                            uint2* __restrict__ chain)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
+        const uint64_t kp = key[p];
+        const uint32_t il = (uint32_t)(kp & 63u);
+        const bool more = p + 1 < nnz && !head[p + 1];
+        if (head[p]) {
+            const uint64_t g = kp >> 18;
+            const uint32_t v = rank[p] - 1u;
+            const int64_t slot = (int64_t)dir_sets[g] * E + (int64_t)(v - first_visit[g]);
+            const uint32_t jl = (uint32_t)((kp >> 6) & 0xFFFu);
+            rec[slot] = make_uint2(__float_as_uint(val[p]),
+                                   (jl * (uint32_t)LPV) | (il << kVisitSrcShift) | (more ? kVisitHasExtra : 0u));
+            if (more) {
+                const bool more2 = p + 2 < nnz && !head[p + 2];
+                const uint32_t il1 = (uint32_t)(key[p + 1] & 63u);
+                extra1[slot] = make_uint2(__float_as_uint(val[p + 1]),
+                                          il1 | (more2 ? (kExtraMore | (chain_pos[p + 2] << kExtraNextShift)) : 0u));
+            }
+        } else if (third[p]) {
+            chain[chain_pos[p]] = make_uint2(__float_as_uint(val[p]), il | (more ? kExtraMore : 0u));
+        }
+    }
+}
+
+// ----------------------------------------------------------------------- kernel ----
+
+struct TiledArgs {
+    const float* dY;
+    const void* sp_index;
+    float* dXs;
+    const uint32_t* dir_sets;  // [n_dsets * n_tiles + 1] first set of every (destination set, tile)
+    const uint2* rec;          // [total_sets * E] visit records
+    const uint2* extra1;       // [total_sets * E] second entry of a visit, where it has one
+    const uint2* chain;        // third and later entries
+    int64_t N;
+    int32_t dim, k;
+    int32_t D, n_dsets, n_tiles;
+    int32_t G, C, R, tiles_per_range;  // destination sets per XCD, concurrent source ranges per XCD, ranges, tiles each
+    int32_t atomic_out;
+    int32_t debug;
+};
+
+// PPL (4 or 8) consecutive sp_index entries, fetched with as few loads as their width allows
+template <typename IdxT, int PPL>
+struct IdxVec;
+template <>
+struct IdxVec<uint8_t, 4> {
+    uint32_t w;
+    __device__ __forceinline__ void load(const void* p) { w = *reinterpret_cast<const uint32_t*>(p); }
+    __device__ __forceinline__ uint32_t get(int i) const { return (w >> (8 * i)) & 0xFFu; }
+};
+template <>
+struct IdxVec<uint8_t, 8> {
+    uint2 w;
+    __device__ __forceinline__ void load(const void* p) { w = *reinterpret_cast<const uint2*>(p); }
+    __device__ __forceinline__ uint32_t get(int i) const { return ((i < 4 ? w.x : w.y) >> (8 * (i & 3))) & 0xFFu; }
+};
+template <>
+struct IdxVec<uint16_t, 4> {
+    uint2 w;
+    __device__ __forceinline__ void load(const void* p) { w = *reinterpret_cast<const uint2*>(p); }
+    __device__ __forceinline__ uint32_t get(int i) const { return ((i < 2 ? w.x : w.y) >> (16 * (i & 1))) & 0xFFFFu; }
+};
+template <>
+struct IdxVec<uint16_t, 8> {
+    uint4 w;
+    __device__ __forceinline__ void load(const void* p) { w = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ uint32_t get(int i) const
+    {
+        const uint32_t x = i < 2 ? w.x : i < 4 ? w.y : i < 6 ? w.z : w.w;
+        return (x >> (16 * (i & 1))) & 0xFFFFu;
+    }
+};
+template <>
+struct IdxVec<int32_t, 4> {
+    uint4 w;
+    __device__ __forceinline__ void load(const void* p) { w = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ uint32_t get(int i) const { return i == 0 ? w.x : i == 1 ? w.y : i == 2 ? w.z : w.w; }
+};
+template <>
+struct IdxVec<int32_t, 8> {
+    uint4 w0, w1;
+    __device__ __forceinline__ void load(const void* p)
+    {
+        w0 = reinterpret_cast<const uint4*>(p)[0];
+        w1 = reinterpret_cast<const uint4*>(p)[1];
+    }
+    __device__ __forceinline__ uint32_t get(int i) const
+    {
+        const uint4& w = i < 4 ? w0 : w1;
+        return (i & 3) == 0 ? w.x : (i & 3) == 1 ? w.y : (i & 3) == 2 ? w.z : w.w;
+    }
+};
+
+// DIMC: hidden width when known at compile time (LDS and row offsets become immediates), 0 = a.dim;
+// RC: 256-column chunks that cover a dY row (dim <= RC * 256); PPL: CBSR positions per lane (4 or 8)
+//
+// A wavefront on its own issues at most one instruction every four clocks or so, and every SIMD here hosts one
+// accumulating and one loading wavefront, so the instruction count per tile and per set is what this kernel's time
+// follows: addresses are kept as a uniform base (scalar registers, advanced with scalar adds) plus a fixed 32-bit lane
+// offset, the lists are padded so that reading ahead needs no clamping, and nothing is recomputed per tile.
+template <int DIMC, int RC, int PPL, typename IdxT>
+__global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int dim = DIMC ? DIMC : a.dim, k = a.k, D = a.D;
+    constexpr bool FULL = DIMC == RC * 256;
+
+    // workgroup b runs on XCD b % 8; the workgroups of an XCD that are resident together work on the same source
+    // range(s), G destination sets each, so that a dY row is pulled into that XCD's L2 once per round
+    const int b = blockIdx.x, xcd = b & 7, m = b >> 3;
+    const int per_round = a.C * a.G;
+    const int round = m / per_round, slot = m - round * per_round;
+    const int c = slot / a.G, gi = slot - c * a.G;
+    const int range = round * a.C + c, d = xcd + 8 * gi;
+    if (range >= a.R || d >= a.n_dsets) return;
+    const int t0 = range * a.tiles_per_range, t1 = min(a.n_tiles, t0 + a.tiles_per_range);
+    if (t0 >= t1) return;
+    const int64_t dest0 = (int64_t)d * D;
+    const int Dn = (int)min((int64_t)D, a.N - dest0);
+
+    const int acc_floats = (D * k + 3) & ~3;
+    float* __restrict__ acc = lds;
+    float* __restrict__ rows = lds + acc_floats;  // two buffers of kTileRows rows
+    for (int i = tid; i < acc_floats / 4; i += kTiledThreads) reinterpret_cast<float4*>(acc)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+
+    // Barrier protocol: barrier number t (t = t0 .. t1-1) is passed by the loaders after they have written tile t and
+    // by the accumulators before they start on tile t, i.e. after they have finished tile t-1.  Every wavefront
+    // executes exactly t1 - t0 of them, whatever its role.
+    if (wave == kAccWaves + kLoadWaves) {
+        // ---- prefetching wavefront ----
+        // The workgroups of an XCD that sweep one source range move as a pack: whoever is first takes the miss to
+        // memory, the others hit L2 and catch up, so the pack would advance at the rate one CU can miss (its
+        // loads in flight / memory latency).  Instead every workgroup of the pack touches its 1/G share of the
+        // cache lines of the tiles kPrefetchAhead ahead (one dword per 128-byte line), which pulls them into L2 with
+        // G times as many misses in flight.  The loaded values are not used.
+        const int64_t row_bytes = (int64_t)dim * 4, total_bytes = a.N * row_bytes;
+        const int64_t lines_per_group = (kPrefetchGroup * kTileRows * row_bytes + 127) / 128;
+        const int pf_loads = (a.G >= 8 && !(a.debug & 4)) ? (int)min((int64_t)4, (lines_per_group / a.G + kWave - 1) / kWave) : 0;
+        uint32_t got[4] = {0u, 0u, 0u, 0u};
+        for (int tile = t0; tile < t1; ++tile) {
+            if (((tile - t0) & (kPrefetchGroup - 1)) == 0 && pf_loads) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(got[j]));  // the previous round has landed
+                const int64_t base = (int64_t)(tile + kPrefetchAhead) * kTileRows * row_bytes;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t off = base + ((int64_t)(j * kWave + lane) * a.G + gi) * 128;
+                    if (j < pf_loads && off + 4 <= total_bytes && tile + kPrefetchAhead < t1)
+                        got[j] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(a.dY) + off);
+                }
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(got[j]));
+    } else if (wave >= kAccWaves) {
+        // ---- loading wavefronts: tile t -> row buffer t & 1 ----
+        constexpr int RP = kTileRows / kLoadWaves;  // rows per wavefront and tile
+        const int lw = wave - kAccWaves;
+        static_assert(kRowQueue == 4, "the queue below is written out for four tiles");
+        float4 q0[RP][RC], q1[RP][RC], q2[RP][RC], q3[RP][RC];  // named, not indexed: they must stay in registers
+        const uint32_t lane_bytes = (uint32_t)lane * 16u;
+        bool col_ok[RC];
+#pragma unroll
+        for (int cc = 0; cc < RC; ++cc) col_ok[cc] = FULL || cc * 256 + lane * 4 < dim;
+        const uint32_t row_bytes = (uint32_t)dim * 4u;
+        const int64_t tile_bytes = (int64_t)kTileRows * row_bytes;
+        // uniform address of this wavefront's first row of tile 0
+        const char* const src0 = reinterpret_cast<const char*>(a.dY) + (int64_t)(lw * RP) * row_bytes;
+        char* const dst0 = reinterpret_cast<char*>(rows) + lw * RP * row_bytes + lane_bytes;
+        const int last_full = (int)(a.N / kTileRows);  // tiles below this one have all their rows
+        const int t1m = min(t1, last_full);            // the queue handles the full tiles [t0, t1m)
+        // A step stores the oldest tile of the queue and issues the tile kRowQueue ahead.  Tiles past the last full one
+        // are replaced by the last full one (loaded, never used), so that every step issues the same loads and the
+        // compiler can wait for exactly the oldest tile in the queue.
+#define MAXK_TILED_ISSUE(Q, TILE)                                                                             \
+    {                                                                                                         \
+        const char* const src = src0 + (int64_t)min((TILE), last_full - 1) * tile_bytes;                      \
+        _Pragma("unroll") for (int rr = 0; rr < RP; ++rr)                                                     \
+            _Pragma("unroll") for (int cc = 0; cc < RC; ++cc)                                                 \
+                if (col_ok[cc])                                                                               \
+                    Q[rr][cc] = *reinterpret_cast<const float4*>(src + (rr * row_bytes + cc * 1024u + lane_bytes)); \
+    }
+#define MAXK_TILED_STORE(Q, TILE)                                                                             \
+    {                                                                                                         \
+        char* const dst = dst0 + ((TILE) & 1) * (kTileRows * row_bytes);                                      \
+        _Pragma("unroll") for (int rr = 0; rr < RP; ++rr)                                                     \
+            _Pragma("unroll") for (int cc = 0; cc < RC; ++cc)                                                 \
+                if (col_ok[cc]) *reinterpret_cast<float4*>(dst + rr * row_bytes + cc * 1024u) = Q[rr][cc];    \
+    }
+#pragma unroll
+        for (int rr = 0; rr < RP; ++rr)
+#pragma unroll
+            for (int cc = 0; cc < RC; ++cc) q0[rr][cc] = q1[rr][cc] = q2[rr][cc] = q3[rr][cc] = make_float4(0.f, 0.f, 0.f, 0.f);
+        int base = t0;
+        if (t0 < t1m) {
+            MAXK_TILED_ISSUE(q0, t0)
+            MAXK_TILED_ISSUE(q1, t0 + 1)
+            MAXK_TILED_ISSUE(q2, t0 + 2)
+            MAXK_TILED_ISSUE(q3, t0 + 3)
+#define MAXK_TILED_STEP(Q, TILE) \
+    MAXK_TILED_STORE(Q, TILE)    \
+    MAXK_TILED_ISSUE(Q, (TILE) + kRowQueue) \
+    __syncthreads();
+            for (; base + kRowQueue <= t1m; base += kRowQueue) {
+                MAXK_TILED_STEP(q0, base)
+                MAXK_TILED_STEP(q1, base + 1)
+                MAXK_TILED_STEP(q2, base + 2)
+                MAXK_TILED_STEP(q3, base + 3)
+            }
+#undef MAXK_TILED_STEP
+            if (base < t1m) { MAXK_TILED_STORE(q0, base) __syncthreads(); }
+            if (base + 1 < t1m) { MAXK_TILED_STORE(q1, base + 1) __syncthreads(); }
+            if (base + 2 < t1m) { MAXK_TILED_STORE(q2, base + 2) __syncthreads(); }
+        }
+        if (t1m < t1) {
+            // the one tile that is cut short by the end of dY: loaded directly, row by row
+            const int tile = t1m;
+#pragma unroll
+            for (int rr = 0; rr < RP; ++rr) {
+                const int64_t row = (int64_t)tile * kTileRows + lw * RP + rr;
+#pragma unroll
+                for (int cc = 0; cc < RC; ++cc) {
+                    float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (row < a.N && col_ok[cc])
+                        x = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(a.dY) + row * row_bytes + cc * 1024u + lane_bytes);
+                    q0[rr][cc] = x;
+                }
+            }
+            MAXK_TILED_STORE(q0, tile)
+            __syncthreads();
+        }
+#undef MAXK_TILED_ISSUE
+#undef MAXK_TILED_STORE
+    } else {
+        // ---- accumulating wavefronts ----
+        constexpr int NQ = PPL / 4;  // float4 pieces of a lane's accumulators
+        const int LPV = k / PPL, E = kWave / LPV;
+        const int g = lane / LPV, q = lane - g * LPV;
+        const bool lane_on = g < E;
+        const int gs = lane_on ? g : 0;
+        // The directory is read through the constant address space: it does not change while the kernel runs, its
+        // addresses are wave-uniform, and so the reads become scalar loads, which do not queue behind the vector
+        // loads in flight (a vector load here would have to wait for all of them at every tile).
+        typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
+        const const_u32_ptr dt = (const_u32_ptr)(a.dir_sets + (int64_t)d * a.n_tiles);
+        // Set s of the workgroup's list goes to wavefront s % 8, whatever tile it belongs to: this wavefront's sets are
+        // first + 8 i, i = 0 .. n_it - 1
+        const uint32_t u0 = dt[t0], u1 = dt[t1];
+        const uint32_t first = u0 + (((uint32_t)wave - u0) & (uint32_t)(kAccWaves - 1));
+        const int n_it = ((a.debug & 2) || first >= u1) ? 0 : (int)((u1 - first + kAccWaves - 1) / kAccWaves);
+        int tile = t0;
+        uint32_t s_end = dt[t0 + 1];                 // first set past `tile`
+        uint32_t s_end_next = dt[t0 + 2];            // (the directory has two spare entries at its end)
+        const_u32_ptr dt_next = dt + (t0 + 3);       // where the s_end_next after that is read from
+        // uniform bases + fixed lane offsets (bytes)
+        const int64_t set_bytes = (int64_t)E * 8;                               // one set of records
+        const int64_t step_bytes = set_bytes * kAccWaves;                       // from one of this wavefront's sets to the next
+        const uint32_t rec_lane = (uint32_t)gs * 8u;
+        const char* rec_at = reinterpret_cast<const char*>(a.rec) + (int64_t)first * set_bytes;      // set being fetched
+        const char* ext_at = reinterpret_cast<const char*>(a.extra1) + (int64_t)first * set_bytes;   // set whose columns are fetched
+        const char* const idx_at = reinterpret_cast<const char*>(a.sp_index) + dest0 * k * (int64_t)sizeof(IdxT);
+        const uint32_t idx_lane = (uint32_t)q * (uint32_t)(PPL * sizeof(IdxT));
+        char* const acc_lane = reinterpret_cast<char*>(acc) + q * (4 * PPL);
+        const char* const rows_b = reinterpret_cast<const char*>(rows);
+        const uint32_t row_bytes = (uint32_t)dim * 4u, buf_bytes = kTileRows * row_bytes;
+        __syncthreads();  // barrier t0: the rows of tile t0 are in buffer t0 & 1
+
+        if (n_it > 0) {
+            static_assert(kRecAhead == 8 && kIdxAhead == 4, "the queues below are written out for these depths");
+            uint2 rq0, rq1, rq2, rq3, rq4, rq5, rq6, rq7;  // named, not indexed: they must stay in registers
+            IdxVec<IdxT, PPL> iq0, iq1, iq2, iq3;
+            uint2 xq0, xq1, xq2, xq3;
+            // the record arrays end with kRecAhead * 8 padding sets, so fetching ahead of the list needs no clamp
+#define MAXK_TILED_FETCH_REC(RQ)                                   \
+    RQ = *reinterpret_cast<const uint2*>(rec_at + rec_lane);       \
+    rec_at += step_bytes;
+// the second-entry array is read for every set, whether a visit has a second entry or not (lanes without one read
+// the set's first slot): a load that is issued only sometimes would keep the compiler from counting the loads in
+// flight, and it would then wait for younger ones than it needs
+#define MAXK_TILED_FETCH_IDX(RQ, IQ, XQ)                                                                              \
+    IQ.load(idx_at + ((RQ.y & kVisitAccMask) * (uint32_t)(PPL * sizeof(IdxT)) + idx_lane));                          \
+    XQ = *reinterpret_cast<const uint2*>(ext_at + ((RQ.y & kVisitHasExtra) ? rec_lane : 0u));                         \
+    ext_at += step_bytes;
+            MAXK_TILED_FETCH_REC(rq0) MAXK_TILED_FETCH_REC(rq1) MAXK_TILED_FETCH_REC(rq2) MAXK_TILED_FETCH_REC(rq3)
+            MAXK_TILED_FETCH_REC(rq4) MAXK_TILED_FETCH_REC(rq5) MAXK_TILED_FETCH_REC(rq6) MAXK_TILED_FETCH_REC(rq7)
+            xq0 = xq1 = xq2 = xq3 = make_uint2(0u, 0u);
+            MAXK_TILED_FETCH_IDX(rq0, iq0, xq0) MAXK_TILED_FETCH_IDX(rq1, iq1, xq1)
+            MAXK_TILED_FETCH_IDX(rq2, iq2, xq2) MAXK_TILED_FETCH_IDX(rq3, iq3, xq3)
+#define MAXK_TILED_ADD(V, SRCROW)                                                                   \
+    {                                                                                               \
+        const char* const row = buf + __umul24((SRCROW), row_bytes);                                \
+        const float v = (V);                                                                        \
+        _Pragma("unroll") for (int n = 0; n < NQ; ++n) {                                            \
+            av[n].x += v * *reinterpret_cast<const float*>(row + cb[4 * n]);                        \
+            av[n].y += v * *reinterpret_cast<const float*>(row + cb[4 * n + 1]);                    \
+            av[n].z += v * *reinterpret_cast<const float*>(row + cb[4 * n + 2]);                    \
+            av[n].w += v * *reinterpret_cast<const float*>(row + cb[4 * n + 3]);                    \
+        }                                                                                           \
+    }
+            // one set: take the oldest queue entries, refill the queues (the same loads every time, so that the
+            // compiler can count them), cross into the set's tile, accumulate
+#define MAXK_TILED_SET(RQ, RQ_AHEAD, IQ, XQ, IT)                                                                      \
+    {                                                                                                                 \
+        const uint2 cur = RQ;                                                                                         \
+        const IdxVec<IdxT, PPL> ci = IQ;                                                                              \
+        const uint2 cx = XQ;                                                                                          \
+        MAXK_TILED_FETCH_REC(RQ)                                                                                      \
+        MAXK_TILED_FETCH_IDX(RQ_AHEAD, IQ, XQ)                                                                        \
+        while (first + (uint32_t)(IT) * kAccWaves >= s_end) { /* next tile: everyone meets at one barrier per tile */ \
+            ++tile;                                                                                                   \
+            s_end = s_end_next;                                                                                       \
+            __syncthreads();                                                                                          \
+            s_end_next = *dt_next++; /* asked for after the barrier, needed at the next one */                        \
+        }                                                                                                             \
+        if (lane_on && !(cur.y & kVisitNull) && !(a.debug & 16)) {                                                    \
+            const char* const buf = rows_b + (tile & 1) * buf_bytes;                                                  \
+            float4* const ap = reinterpret_cast<float4*>(acc_lane + (cur.y & kVisitAccMask) * (uint32_t)(4 * PPL));   \
+            float4 av[NQ];                                                                                            \
+            uint32_t cb[PPL]; /* byte offsets of the lane's columns within a row */                                   \
+            _Pragma("unroll") for (int n = 0; n < NQ; ++n) av[n] = ap[n];                                             \
+            _Pragma("unroll") for (int i = 0; i < PPL; ++i) cb[i] = ci.get(i) * 4u;                                   \
+            MAXK_TILED_ADD(__uint_as_float(cur.x), (cur.y >> kVisitSrcShift) & 63u)                                   \
+            if (cur.y & kVisitHasExtra) {                                                                             \
+                MAXK_TILED_ADD(__uint_as_float(cx.x), cx.y & 63u)                                                     \
+                if (cx.y & kExtraMore) {                                                                              \
+                    uint32_t at = (cx.y >> kExtraNextShift) & 0x1FFFFFFu;                                             \
+                    for (;;) {                                                                                        \
+                        const uint2 e = a.chain[at++];                                                                \
+                        MAXK_TILED_ADD(__uint_as_float(e.x), e.y & 63u)                                               \
+                        if (!(e.y & kExtraMore)) break;                                                               \
+                    }                                                                                                 \
+                }                                                                                                     \
+            }                                                                                                         \
+            _Pragma("unroll") for (int n = 0; n < NQ; ++n) ap[n] = av[n];                                             \
+        }                                                                                                             \
+    }
+            int ib = 0;
+            for (; ib + kRecAhead <= n_it; ib += kRecAhead) {
+                MAXK_TILED_SET(rq0, rq4, iq0, xq0, ib)
+                MAXK_TILED_SET(rq1, rq5, iq1, xq1, ib + 1)
+                MAXK_TILED_SET(rq2, rq6, iq2, xq2, ib + 2)
+                MAXK_TILED_SET(rq3, rq7, iq3, xq3, ib + 3)
+                MAXK_TILED_SET(rq4, rq0, iq0, xq0, ib + 4)
+                MAXK_TILED_SET(rq5, rq1, iq1, xq1, ib + 5)
+                MAXK_TILED_SET(rq6, rq2, iq2, xq2, ib + 6)
+                MAXK_TILED_SET(rq7, rq3, iq3, xq3, ib + 7)
+            }
+            if (ib < n_it) MAXK_TILED_SET(rq0, rq4, iq0, xq0, ib)
+            if (ib + 1 < n_it) MAXK_TILED_SET(rq1, rq5, iq1, xq1, ib + 1)
+            if (ib + 2 < n_it) MAXK_TILED_SET(rq2, rq6, iq2, xq2, ib + 2)
+            if (ib + 3 < n_it) MAXK_TILED_SET(rq3, rq7, iq3, xq3, ib + 3)
+            if (ib + 4 < n_it) MAXK_TILED_SET(rq4, rq0, iq0, xq0, ib + 4)
+            if (ib + 5 < n_it) MAXK_TILED_SET(rq5, rq1, iq1, xq1, ib + 5)
+            if (ib + 6 < n_it) MAXK_TILED_SET(rq6, rq2, iq2, xq2, ib + 6)
+#undef MAXK_TILED_FETCH_REC
+#undef MAXK_TILED_FETCH_IDX
+#undef MAXK_TILED_SET
+#undef MAXK_TILED_ADD
+        }
+        while (tile < t1 - 1) {
+            ++tile;
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+    float* __restrict__ out = a.dXs + dest0 * k;
+    const int n_out = Dn * k;
+    if (a.atomic_out) {
+        for (int i = tid; i < n_out; i += kTiledThreads) unsafeAtomicAdd(out + i, acc[i]);
+    } else {
+        for (int i = tid; i < n_out; i += kTiledThreads) out[i] = acc[i];
+    }
+}
+
+template <int DIMC, int RC, int PPL, typename IdxT>
+maxk_status launch_tiled_t(const TiledArgs& a, size_t lds_bytes, hipStream_t s)
+{
+    static bool attr_set = false;  // per instantiation; the attribute is idempotent
+    if (!attr_set) {
+        MAXK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_tiled_kernel<DIMC, RC, PPL, IdxT>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+        attr_set = true;
+    }
+    const int rounds = (a.R + a.C - 1) / a.C;
+    const int64_t grid = (int64_t)8 * a.C * a.G * rounds;
+    if (grid > 0x7FFFFFFFll) return MAXK_UNSUPPORTED;
+    hipLaunchKernelGGL((bwd_tiled_kernel<DIMC, RC, PPL, IdxT>), dim3((unsigned)grid), dim3(kTiledThreads), lds_bytes, s, a);
+    MAXK_LAUNCH_CHECK();
+    return MAXK_OK;
+}
+
+}  // namespace
+
+// CBSR positions one lane works on: 8 where k allows, so that a wave instruction (and the loads that feed it)
+// covers twice as many visits
+int tiled_positions_per_lane(int k) { return k % 8 == 0 ? 8 : 4; }
+
+void free_tiled(TiledSet& T)
+{
+    (void)hipFree(T.d_dir_sets);
+    (void)hipFree(T.d_rec);
+    (void)hipFree(T.d_extra1);
+    (void)hipFree(T.d_chain);
+    T = TiledSet();
+}
+
+bool tiled_shape(int64_t N, int dim, int k, int& D, int& n_dsets)
+{
+    if (N < 1 || k % 4 != 0 || k < 4 || k > 256 || dim % 4 != 0 || dim > 512) return false;
+    const int64_t row_bytes = 2ll * kTileRows * dim * 4;
+    const int64_t dmax = std::min<int64_t>((kLdsBytes - row_bytes - 256) / (4ll * k), 4096);
+    if (dmax < 64) return false;
+    int64_t S = 8;
+    while ((N + S - 1) / S > dmax) S *= 2;
+    if (S > 65536) return false;
+    D = (int)((N + S - 1) / S);
+    n_dsets = (int)((N + D - 1) / D);
+    return true;
+}
+
+// Builds the visit lists for destination sets of D nodes and k/4 lanes per visit.  Synchronises the device.
+maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_csc_ptr, const int32_t* d_csc_src,
+                        const float* d_csc_val, int D, int k)
+{
+    const int LPV = k / tiled_positions_per_lane(k), E = kWave / LPV;
+    MAXK_HIP_TRY(hipDeviceSynchronize());
+    const int64_t n_dsets = (N + D - 1) / D, n_tiles = (N + kTileRows - 1) / kTileRows;
+    const int64_t n_groups = n_dsets * n_tiles;
+    if (n_groups + 1 > ((int64_t)1 << 28) || nnz < 1 || (int64_t)D * LPV > (int64_t)kVisitAccMask + 1) return MAXK_UNSUPPORTED;
+    hipStream_t s = nullptr;
+    uint64_t *d_key = nullptr, *d_key_sorted = nullptr;
+    float* d_val_sorted = nullptr;
+    uint32_t *d_head = nullptr, *d_rank = nullptr, *d_third = nullptr, *d_chain_pos = nullptr, *d_first_visit = nullptr,
+             *d_sets = nullptr;
+    void* d_tmp = nullptr;
+    auto cleanup = [&]() {
+        (void)hipFree(d_key); (void)hipFree(d_key_sorted); (void)hipFree(d_val_sorted); (void)hipFree(d_head);
+        (void)hipFree(d_rank); (void)hipFree(d_third); (void)hipFree(d_chain_pos); (void)hipFree(d_first_visit);
+        (void)hipFree(d_sets); (void)hipFree(d_tmp);
+    };
+#define MAXK_TRY_CLEAN(expr)                                                           \
+    do {                                                                               \
+        hipError_t _e = (expr);                                                        \
+        if (_e != hipSuccess) { cleanup(); free_tiled(T); return hip_fail(_e); }       \
+    } while (0)
+    const unsigned blocks = (unsigned)std::min<int64_t>((nnz + 255) / 256, 65536);
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_key, sizeof(uint64_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_key_sorted, sizeof(uint64_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_val_sorted, sizeof(float) * (size_t)nnz));
+    hipLaunchKernelGGL(tiled_keys_kernel, dim3(blocks), dim3(256), 0, s, d_csc_ptr, d_csc_src, N, nnz, D, (int32_t)n_tiles,
+                       d_key);
+    MAXK_TRY_CLEAN(hipGetLastError());
+    int end_bit = 19;
+    while (end_bit < 64 && ((uint64_t)1 << (end_bit - 18)) < (uint64_t)n_groups) ++end_bit;
+    size_t tmp_bytes = 0;
+    MAXK_TRY_CLEAN(rocprim::radix_sort_pairs(nullptr, tmp_bytes, d_key, d_key_sorted, d_csc_val, d_val_sorted, (size_t)nnz,
+                                             0, (unsigned)end_bit, s));
+    MAXK_TRY_CLEAN(hipMalloc(&d_tmp, tmp_bytes ? tmp_bytes : 16));
+    MAXK_TRY_CLEAN(rocprim::radix_sort_pairs(d_tmp, tmp_bytes, d_key, d_key_sorted, d_csc_val, d_val_sorted, (size_t)nnz,
+                                             0, (unsigned)end_bit, s));
+    MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+    (void)hipFree(d_tmp); d_tmp = nullptr;
+    (void)hipFree(d_key); d_key = nullptr;
+
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_head, sizeof(uint32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_rank, sizeof(uint32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_third, sizeof(uint32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_chain_pos, sizeof(uint32_t) * (size_t)nnz));
+    hipLaunchKernelGGL(tiled_flags_kernel, dim3(blocks), dim3(256), 0, s, d_key_sorted, nnz, d_head, d_third);
+    MAXK_TRY_CLEAN(hipGetLastError());
+    tmp_bytes = 0;
+    MAXK_TRY_CLEAN(rocprim::inclusive_scan(nullptr, tmp_bytes, d_head, d_rank, (size_t)nnz, rocprim::plus<uint32_t>(), s));
+    size_t tmp2 = 0;
+    MAXK_TRY_CLEAN(rocprim::exclusive_scan(nullptr, tmp2, d_third, d_chain_pos, 0u, (size_t)nnz, rocprim::plus<uint32_t>(), s));
+    tmp_bytes = std::max(tmp_bytes, tmp2);
+    MAXK_TRY_CLEAN(hipMalloc(&d_tmp, tmp_bytes ? tmp_bytes : 16));
+    MAXK_TRY_CLEAN(rocprim::inclusive_scan(d_tmp, tmp_bytes, d_head, d_rank, (size_t)nnz, rocprim::plus<uint32_t>(), s));
+    MAXK_TRY_CLEAN(rocprim::exclusive_scan(d_tmp, tmp2, d_third, d_chain_pos, 0u, (size_t)nnz, rocprim::plus<uint32_t>(), s));
+    uint32_t n_visits = 0, last_third = 0, last_chain = 0;
+    MAXK_TRY_CLEAN(hipMemcpyAsync(&n_visits, d_rank + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    MAXK_TRY_CLEAN(hipMemcpyAsync(&last_third, d_third + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    MAXK_TRY_CLEAN(hipMemcpyAsync(&last_chain, d_chain_pos + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+    (void)hipFree(d_tmp); d_tmp = nullptr;
+    const int64_t n_chain = (int64_t)last_chain + last_third;
+    if (n_chain >= kMaxChain) { cleanup(); return MAXK_UNSUPPORTED; }
+
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_first_visit, sizeof(uint32_t) * (size_t)(n_groups + 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_sets, sizeof(uint32_t) * (size_t)(n_groups + 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_dir_sets, sizeof(uint32_t) * (size_t)(n_groups + 4)));
+    MAXK_TRY_CLEAN(hipMemsetAsync(T.d_dir_sets + n_groups, 0xFF, sizeof(uint32_t) * 4, s));  // spare entries: read, never used
+    hipLaunchKernelGGL(tiled_groups_kernel, dim3((unsigned)((n_groups + 1 + 255) / 256)), dim3(256), 0, s, d_key_sorted,
+                       d_rank, nnz, n_groups, E, n_visits, d_first_visit, d_sets);
+    MAXK_TRY_CLEAN(hipGetLastError());
+    tmp_bytes = 0;
+    MAXK_TRY_CLEAN(rocprim::exclusive_scan(nullptr, tmp_bytes, d_sets, T.d_dir_sets, 0u, (size_t)(n_groups + 1),
+                                           rocprim::plus<uint32_t>(), s));
+    MAXK_TRY_CLEAN(hipMalloc(&d_tmp, tmp_bytes ? tmp_bytes : 16));
+    MAXK_TRY_CLEAN(rocprim::exclusive_scan(d_tmp, tmp_bytes, d_sets, T.d_dir_sets, 0u, (size_t)(n_groups + 1),
+                                           rocprim::plus<uint32_t>(), s));
+    uint32_t total_sets = 0;
+    MAXK_TRY_CLEAN(hipMemcpyAsync(&total_sets, T.d_dir_sets + n_groups, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+    // the set count is a 32-bit sum: refuse graphs where it could have wrapped
+    if ((int64_t)n_visits > (int64_t)total_sets * E ||
+        (int64_t)total_sets > (int64_t)n_visits) {
+        cleanup(); free_tiled(T); return MAXK_UNSUPPORTED;
+    }
+    // padding sets at the end: the kernel fetches kRecAhead of a wavefront's sets ahead without clamping
+    const int64_t n_slots = ((int64_t)total_sets + (kRecAhead + 1) * kAccWaves) * E;
+    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_rec, sizeof(uint2) * (size_t)std::max<int64_t>(n_slots, 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_extra1, sizeof(uint2) * (size_t)std::max<int64_t>(n_slots, 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_chain, sizeof(uint2) * (size_t)(n_chain + 1)));
+    hipLaunchKernelGGL(tiled_fill_null_kernel, dim3((unsigned)std::min<int64_t>((n_slots + 255) / 256 + 1, 65536)), dim3(256),
+                       0, s, T.d_rec, n_slots);
+    hipLaunchKernelGGL(tiled_records_kernel, dim3(blocks), dim3(256), 0, s, d_key_sorted, d_val_sorted, d_head, d_rank,
+                       d_third, d_chain_pos, nnz, E, LPV, d_first_visit, T.d_dir_sets, T.d_rec, T.d_extra1, T.d_chain);
+    MAXK_TRY_CLEAN(hipGetLastError());
+    MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+#undef MAXK_TRY_CLEAN
+    cleanup();
+    T.D = D;
+    T.E = E;
+    T.LPV = LPV;
+    T.n_dsets = (int32_t)n_dsets;
+    T.n_tiles = (int32_t)n_tiles;
+    T.total_sets = total_sets;
+    T.n_visits = n_visits;
+    T.n_chain = n_chain;
+    return MAXK_OK;
+}
+
+bool tiled_supports(const void* dY, int value_type, const void* sp_index, int index_bytes, int dim, int k)
+{
+    return value_type == MAXK_VALUE_F32 && k % 4 == 0 && k >= 4 && k <= 256 && dim % 4 == 0 && dim <= 512 &&
+           aligned(dY, 16) && aligned(sp_index, std::min<size_t>(16, (size_t)tiled_positions_per_lane(k) * index_bytes));
+}
+
+maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, const void* sp_index, int index_bytes,
+                             int64_t N, int dim, int k, float* dXs, hipStream_t s)
+{
+    if (!tiled_supports(dY, value_type, sp_index, index_bytes, dim, k) || T.LPV != k / tiled_positions_per_lane(k)) return MAXK_UNSUPPORTED;
+    TiledArgs a;
+    a.dY = (const float*)dY;
+    a.sp_index = sp_index;
+    a.dXs = dXs;
+    a.dir_sets = T.d_dir_sets;
+    a.rec = T.d_rec;
+    a.extra1 = T.d_extra1;
+    a.chain = T.d_chain;
+    a.N = N;
+    a.dim = dim;
+    a.k = k;
+    a.D = T.D;
+    a.n_dsets = T.n_dsets;
+    a.n_tiles = T.n_tiles;
+    // destination sets per XCD, and how many source ranges the 32 CUs of an XCD work on at a time
+    a.G = (T.n_dsets + 7) / 8;
+    a.C = std::max(1, 32 / a.G);
+    a.R = std::min<int>(a.C, std::max<int>(1, T.n_tiles / 8));
+    a.tiles_per_range = (T.n_tiles + a.R - 1) / a.R;
+    a.R = (T.n_tiles + a.tiles_per_range - 1) / a.tiles_per_range;
+    a.atomic_out = a.R > 1;
+    a.debug = getenv("MAXK_TILED_DEBUG") ? atoi(getenv("MAXK_TILED_DEBUG")) : 0;
+    if (a.atomic_out) {
+        const maxk_status st = launch_fill_zero(dXs, N * (int64_t)k, s);
+        if (st != MAXK_OK) return st;
+    }
+    const size_t lds_bytes = sizeof(float) * ((size_t)((T.D * k + 3) & ~3) + 2 * (size_t)kTileRows * dim);
+    if (lds_bytes > (size_t)kLdsBytes) return MAXK_UNSUPPORTED;
+#define MAXK_TILED_I(DIMC, RC, PPL)                                                                               \
+    (index_bytes == 1 ? launch_tiled_t<DIMC, RC, PPL, uint8_t>(a, lds_bytes, s)                                   \
+     : index_bytes == 2 ? launch_tiled_t<DIMC, RC, PPL, uint16_t>(a, lds_bytes, s)                                \
+                        : launch_tiled_t<DIMC, RC, PPL, int32_t>(a, lds_bytes, s))
+    if (tiled_positions_per_lane(k) == 8) {
+        if (dim == 256) return MAXK_TILED_I(256, 1, 8);
+        if (dim < 256) return MAXK_TILED_I(0, 1, 8);
+        return MAXK_TILED_I(0, 2, 8);
+    }
+    if (dim == 256) return MAXK_TILED_I(256, 1, 4);
+    if (dim < 256) return MAXK_TILED_I(0, 1, 4);
+    return MAXK_TILED_I(0, 2, 4);
+#undef MAXK_TILED_I
+}
+
+}  // namespace maxk

@@ -19,11 +19,13 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = (ROOT / "include" / "maxk.h").read_text()
-    declared = re.findall(r"MAXK_API\s+[\w\s\*]+?\b(\w+)\s*\(", header)
+    declared = []
+    for h in sorted((ROOT / "include").glob("*.h")):
+        names = re.findall(r"MAXK_API\s+[\w\s\*]+?\b(\w+)\s*\(", h.read_text())
+        for name in names:
+            assert hasattr(lib, name), f"{name} declared in {h.name} but not exported"
+        declared += names
     assert len(declared) >= 12
-    for name in declared:
-        assert hasattr(lib, name), f"{name} declared in maxk.h but not exported"
     from paper_2312_08656_amd.binding import EXPORTS
     assert sorted(declared) == sorted(EXPORTS)
 
