@@ -57,13 +57,13 @@ struct SlabSet {
 constexpr int kSlabLongVisit = 32;
 
 // A^T regrouped for the LDS-tiled backward kernel: destinations are cut into sets of D nodes (a workgroup keeps one
-// set's accumulators in LDS), sources into tiles of 16 rows; every non-empty (tile, destination) pair is a visit,
-// listed per (destination set, owner wavefront, tile) and padded to whole wave instructions of E visits.
+// set's accumulators in LDS), sources into tiles of TR rows; every non-empty (tile, destination) pair is a visit,
+// listed per (destination set, tile) and padded to whole wave instructions of E visits.
 struct TiledSet {
-    int32_t D = 0, E = 0, LPV = 0;  // destinations per set; visits per wave instruction; lanes per visit (k / 4)
+    int32_t D = 0, TR = 0, E = 0, LPV = 0;  // destinations per set; rows per tile; visits per wave instruction; lanes per visit
     int32_t n_dsets = 0, n_tiles = 0;
     int64_t total_sets = 0, n_visits = 0, n_chain = 0;
-    uint32_t* d_dir_sets = nullptr;  // [n_dsets * 4 * n_tiles + 1] first wave instruction of each list
+    uint32_t* d_dir_sets = nullptr;  // [n_dsets * n_tiles + 1 (+ spare)] first wave instruction of each list
     uint2* d_rec = nullptr;          // [total_sets * E] visit records (first entry inline)
     uint2* d_extra1 = nullptr;       // [total_sets * E] second entry of a visit
     uint2* d_chain = nullptr;        // [n_chain + 1] third and later entries
@@ -165,11 +165,12 @@ maxk_status launch_bwd_slab_pull(const SlabSet& S, const void* dY, int value_typ
                                  int index_bytes, int64_t N, int dim, int k, float* dXs, hipStream_t s);
 
 // LDS-tiled backward kernel (fp32 dY, k % 4 == 0, dim % 4 == 0, dim <= 512)
-bool tiled_shape(int64_t N, int dim, int k, int& D, int& n_dsets);  // false: this (N, dim, k) is not supported
+struct TiledShape { int D = 0, TR = 0, n_dsets = 0; };
+bool tiled_shape(int64_t N, int dim, int k, int tr_knob, int d_knob, TiledShape& sh);  // false: (N, dim, k) not supported
 int tiled_positions_per_lane(int k);
 bool tiled_supports(const void* dY, int value_type, const void* sp_index, int index_bytes, int dim, int k);
 maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_csc_ptr, const int32_t* d_csc_src,
-                        const float* d_csc_val, int D, int k);
+                        const float* d_csc_val, int D, int TR, int k);
 void free_tiled(TiledSet& T);
 maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, const void* sp_index, int index_bytes,
                              int64_t N, int dim, int k, float* dXs, hipStream_t s);

@@ -45,6 +45,7 @@ struct maxk_graph {
     int32_t chunk = 0;         // tuning knobs, read from the environment once, by maxk_graph_create
     int32_t slab_kb = 0;
     int32_t fwd_pack_max = 0;
+    int32_t tiled_tr = 0, tiled_d = 0;  // 0: the library's choice
     int device = 0;
 };
 
@@ -457,13 +458,13 @@ maxk_status slabs_for(maxk_graph* g, int32_t slab_rows, SlabSet** out)
 
 maxk_status tiled_for(maxk_graph* g, int dim, int k, TiledSet** out)
 {
-    int D = 0, n_dsets = 0;
-    if (!tiled_shape(g->N, dim, k, D, n_dsets)) return MAXK_UNSUPPORTED;
+    TiledShape sh;
+    if (!tiled_shape(g->N, dim, k, g->tiled_tr, g->tiled_d, sh)) return MAXK_UNSUPPORTED;
     for (TiledSet* T : g->tiled_cache)
-        if (T->D == D && T->LPV == k / tiled_positions_per_lane(k)) { *out = T; return MAXK_OK; }
+        if (T->D == sh.D && T->TR == sh.TR && T->LPV == k / tiled_positions_per_lane(k)) { *out = T; return MAXK_OK; }
     TiledSet* T = new (std::nothrow) TiledSet();
     if (!T) return MAXK_OUT_OF_MEMORY;
-    const maxk_status st = build_tiled(*T, g->N, g->nnz, g->d_csc_ptr, g->d_csc_src, g->d_csc_val, D, k);
+    const maxk_status st = build_tiled(*T, g->N, g->nnz, g->d_csc_ptr, g->d_csc_src, g->d_csc_val, sh.D, sh.TR, k);
     if (st != MAXK_OK) { delete T; return st; }
     try { g->tiled_cache.push_back(T); } catch (const std::bad_alloc&) { free_tiled(*T); delete T; return MAXK_OUT_OF_MEMORY; }
     *out = T;
@@ -515,11 +516,11 @@ int auto_bwd_mode(const maxk_graph* g, int dim, int k, int val_bytes = 4, bool t
 {
     // LDS-tiled: a workgroup's wavefront gets nnz * 16 * D / (4 N^2) visits per tile; it pays off once those fill
     // a good part of a wave instruction (64 / (k/4) visits)
-    int D = 0, n_dsets = 0;
-    if (tiled_ok && val_bytes == 4 && g->nnz > 0 && tiled_shape(g->N, dim, k, D, n_dsets)) {
-        const double per_list = (double)g->nnz * 16.0 * D / (4.0 * (double)g->N * (double)g->N);
-        const double n_lists = (double)n_dsets * 4.0 * std::ceil((double)g->N / 16.0);
-        if (per_list >= 0.4 * (64.0 / (k / tiled_positions_per_lane(k))) && n_lists < 2.6e8) return MAXK_BWD_TILED;
+    TiledShape sh;
+    if (tiled_ok && val_bytes == 4 && g->nnz > 0 && tiled_shape(g->N, dim, k, g->tiled_tr, g->tiled_d, sh)) {
+        const double per_tile = (double)g->nnz * sh.TR * sh.D / ((double)g->N * (double)g->N);  // visits per tile
+        const double n_lists = (double)sh.n_dsets * std::ceil((double)g->N / sh.TR);
+        if (per_tile >= 1.6 * (64.0 / (k / tiled_positions_per_lane(k))) && n_lists < 2.6e8) return MAXK_BWD_TILED;
     }
     const double n_slabs = std::ceil((double)g->N / slab_rows_for(g, dim, val_bytes));
     const double entries_per_visit = (double)g->nnz / std::max(1.0, (double)g->N * n_slabs);
@@ -568,6 +569,8 @@ MAXK_API maxk_status maxk_graph_create(maxk_graph** out, int64_t N, int64_t nnz,
     g->chunk = env_int("MAXK_CHUNK", 2048, 64, 1 << 20);  // measured plateau: 2048 and up
     g->slab_kb = env_int("MAXK_SLAB_KB", 3584, 64, 1 << 20);
     g->fwd_pack_max = env_int("MAXK_FWD_PACK_MAX", 96, 0, 1 << 20);
+    g->tiled_tr = env_int("MAXK_TILED_ROWS", 0, 0, 64);
+    g->tiled_d = env_int("MAXK_TILED_DESTS", 0, 0, 4096);
     (void)hipGetDevice(&g->device);
 
     maxk_status st = MAXK_OK;

@@ -36,19 +36,24 @@
 
 #include "common.hpp"
 
+#ifdef MAXK_TILED_PROFILE
+#include <cstdio>
+#define MAXK_PROF_BARRIER() { const long long _t0 = clock64(); __syncthreads(); prof_wait += clock64() - _t0; }
+#else
+#define MAXK_PROF_BARRIER() __syncthreads();
+#endif
+
 namespace maxk {
 namespace {
 
-constexpr int kTileRows = 16;       // source rows per tile
 constexpr int kAccWaves = 8;        // accumulating wavefronts
 constexpr int kLoadWaves = 4;       // loading wavefronts
 constexpr int kTiledThreads = (kAccWaves + kLoadWaves + 1) * kWave;  // + one wavefront that prefetches
 constexpr int kLdsBytes = 160 * 1024;
-constexpr int kRowQueue = 4;        // tiles a loading wavefront keeps in flight
 constexpr int kRecAhead = 8;        // sets between the fetch of a visit record and its use
 constexpr int kIdxAhead = 4;        // sets between the fetch of a visit's CBSR columns and their use
-constexpr int kPrefetchAhead = 32;  // tiles between the L2 prefetch and the loads that use it
-constexpr int kPrefetchGroup = 16;  // tiles covered by one round of prefetch instructions
+constexpr int kPrefetchAheadRows = 512;  // rows between the L2 prefetch and the loads that use it
+constexpr int kPrefetchGroupRows = 256;  // rows covered by one round of prefetch instructions
 
 // second word of a visit record: accumulator row (in units of four floats), source row within the tile, flags
 constexpr uint32_t kVisitAccMask = 0x3FFFu;
@@ -65,7 +70,8 @@ constexpr int64_t kMaxChain = (int64_t)1 << 25;
 // key = ((set * n_tiles + tile) << 18) | dest_local << 6 | src_local, one per in-entry of A^T
 __global__ __launch_bounds__(256) void tiled_keys_kernel(const int32_t* __restrict__ csc_ptr,
                                                          const int32_t* __restrict__ csc_src, int64_t N, int64_t nnz,
-                                                         int32_t D, int32_t n_tiles, uint64_t* __restrict__ key)
+                                                         int32_t D, int32_t tile_rows, int32_t n_tiles,
+                                                         uint64_t* __restrict__ key)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
@@ -76,7 +82,7 @@ __global__ __launch_bounds__(256) void tiled_keys_kernel(const int32_t* __restri
         }
         const int32_t j = (int32_t)lo, i = csc_src[p];
         const int32_t d = j / D, jl = j - d * D;
-        const int32_t tile = i / kTileRows, il = i - tile * kTileRows;
+        const int32_t tile = i / tile_rows, il = i - tile * tile_rows;
         const uint64_t group = (uint64_t)d * (uint64_t)n_tiles + (uint64_t)tile;
         key[p] = (group << 18) | ((uint64_t)jl << 6) | (uint64_t)il;
     }
@@ -179,9 +185,10 @@ struct TiledArgs {
     int64_t N;
     int32_t dim, k;
     int32_t D, n_dsets, n_tiles;
-    int32_t G, C, R, tiles_per_range;  // destination sets per XCD, concurrent source ranges per XCD, ranges, tiles each
+    int32_t G, R, tiles_per_range;  // destination sets per XCD, source ranges, tiles per range
     int32_t atomic_out;
     int32_t debug;
+    long long* prof;
 };
 
 // PPL (4 or 8) consecutive sp_index entries, fetched with as few loads as their width allows
@@ -236,6 +243,7 @@ struct IdxVec<int32_t, 8> {
     }
 };
 
+// TR: source rows per tile (16, 32 or 48);
 // DIMC: hidden width when known at compile time (LDS and row offsets become immediates), 0 = a.dim;
 // RC: 256-column chunks that cover a dY row (dim <= RC * 256); PPL: CBSR positions per lane (4 or 8)
 //
@@ -243,7 +251,7 @@ struct IdxVec<int32_t, 8> {
 // accumulating and one loading wavefront, so the instruction count per tile and per set is what this kernel's time
 // follows: addresses are kept as a uniform base (scalar registers, advanced with scalar adds) plus a fixed 32-bit lane
 // offset, the lists are padded so that reading ahead needs no clamping, and nothing is recomputed per tile.
-template <int DIMC, int RC, int PPL, typename IdxT>
+template <int TR, int DIMC, int RC, int PPL, typename IdxT>
 __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -252,13 +260,12 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
     const int dim = DIMC ? DIMC : a.dim, k = a.k, D = a.D;
     constexpr bool FULL = DIMC == RC * 256;
 
-    // workgroup b runs on XCD b % 8; the workgroups of an XCD that are resident together work on the same source
-    // range(s), G destination sets each, so that a dY row is pulled into that XCD's L2 once per round
+    // Workgroup b runs on XCD b % 8.  Destination set d belongs to XCD d % 8, and an XCD takes its (source range,
+    // destination set) units range by range, so the 32 workgroups that are resident on it together sweep the same
+    // one or two source ranges at the same pace, and a dY row is pulled into that XCD's L2 once per range.
     const int b = blockIdx.x, xcd = b & 7, m = b >> 3;
-    const int per_round = a.C * a.G;
-    const int round = m / per_round, slot = m - round * per_round;
-    const int c = slot / a.G, gi = slot - c * a.G;
-    const int range = round * a.C + c, d = xcd + 8 * gi;
+    const int range = m / a.G, gi = m - range * a.G;
+    const int d = xcd + 8 * gi;
     if (range >= a.R || d >= a.n_dsets) return;
     const int t0 = range * a.tiles_per_range, t1 = min(a.n_tiles, t0 + a.tiles_per_range);
     if (t0 >= t1) return;
@@ -267,13 +274,17 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
 
     const int acc_floats = (D * k + 3) & ~3;
     float* __restrict__ acc = lds;
-    float* __restrict__ rows = lds + acc_floats;  // two buffers of kTileRows rows
+    float* __restrict__ rows = lds + acc_floats;  // two buffers of TR rows
     for (int i = tid; i < acc_floats / 4; i += kTiledThreads) reinterpret_cast<float4*>(acc)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
     // Barrier protocol: barrier number t (t = t0 .. t1-1) is passed by the loaders after they have written tile t and
     // by the accumulators before they start on tile t, i.e. after they have finished tile t-1.  Every wavefront
     // executes exactly t1 - t0 of them, whatever its role.
+#ifdef MAXK_TILED_PROFILE
+    long long prof_wait = 0;
+    const long long prof_start = clock64();
+#endif
     if (wave == kAccWaves + kLoadWaves) {
         // ---- prefetching wavefront ----
         // The workgroups of an XCD that sweep one source range move as a pack: whoever is first takes the miss to
@@ -281,60 +292,67 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         // loads in flight / memory latency).  Instead every workgroup of the pack touches its 1/G share of the
         // cache lines of the tiles kPrefetchAhead ahead (one dword per 128-byte line), which pulls them into L2 with
         // G times as many misses in flight.  The loaded values are not used.
+        constexpr int PG = kPrefetchGroupRows / TR > 0 ? kPrefetchGroupRows / TR : 1;  // tiles per prefetch round
+        constexpr int PA = kPrefetchAheadRows / TR;                                     // tiles ahead
+        const int pack = min(a.G, 32);  // workgroups that share the lines of a round
         const int64_t row_bytes = (int64_t)dim * 4, total_bytes = a.N * row_bytes;
-        const int64_t lines_per_group = (kPrefetchGroup * kTileRows * row_bytes + 127) / 128;
-        const int pf_loads = (a.G >= 8 && !(a.debug & 4)) ? (int)min((int64_t)4, (lines_per_group / a.G + kWave - 1) / kWave) : 0;
+        const int64_t lines_per_group = (PG * TR * row_bytes + 127) / 128;
+        const int pf_loads = (pack >= 8 && !(a.debug & 4)) ? (int)min((int64_t)4, (lines_per_group / pack + kWave - 1) / kWave) : 0;
         uint32_t got[4] = {0u, 0u, 0u, 0u};
+        int countdown = 0;
         for (int tile = t0; tile < t1; ++tile) {
-            if (((tile - t0) & (kPrefetchGroup - 1)) == 0 && pf_loads) {
+            if (countdown == 0 && pf_loads) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(got[j]));  // the previous round has landed
-                const int64_t base = (int64_t)(tile + kPrefetchAhead) * kTileRows * row_bytes;
+                const int64_t base = (int64_t)(tile + PA) * TR * row_bytes;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int64_t off = base + ((int64_t)(j * kWave + lane) * a.G + gi) * 128;
-                    if (j < pf_loads && off + 4 <= total_bytes && tile + kPrefetchAhead < t1)
+                    const int64_t off = base + ((int64_t)(j * kWave + lane) * pack + gi % pack) * 128;
+                    if (j < pf_loads && off + 4 <= total_bytes && tile + PA < t1)
                         got[j] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(a.dY) + off);
                 }
+                countdown = PG;
             }
-            __syncthreads();
+            --countdown;
+            MAXK_PROF_BARRIER()
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(got[j]));
     } else if (wave >= kAccWaves) {
         // ---- loading wavefronts: tile t -> row buffer t & 1 ----
-        constexpr int RP = kTileRows / kLoadWaves;  // rows per wavefront and tile
+        constexpr int RP = TR / kLoadWaves;                    // rows per wavefront and tile
+        constexpr int Q = (TR == 16 && RC == 1) ? 4 : 2;        // tiles this wavefront keeps in flight
+        static_assert(TR % kLoadWaves == 0 && Q * RP * RC * 4 <= 96, "the row queue must fit the register budget");
         const int lw = wave - kAccWaves;
-        static_assert(kRowQueue == 4, "the queue below is written out for four tiles");
         float4 q0[RP][RC], q1[RP][RC], q2[RP][RC], q3[RP][RC];  // named, not indexed: they must stay in registers
         const uint32_t lane_bytes = (uint32_t)lane * 16u;
         bool col_ok[RC];
 #pragma unroll
         for (int cc = 0; cc < RC; ++cc) col_ok[cc] = FULL || cc * 256 + lane * 4 < dim;
         const uint32_t row_bytes = (uint32_t)dim * 4u;
-        const int64_t tile_bytes = (int64_t)kTileRows * row_bytes;
+        const int64_t tile_bytes = (int64_t)TR * row_bytes;
         // uniform address of this wavefront's first row of tile 0
         const char* const src0 = reinterpret_cast<const char*>(a.dY) + (int64_t)(lw * RP) * row_bytes;
         char* const dst0 = reinterpret_cast<char*>(rows) + lw * RP * row_bytes + lane_bytes;
-        const int last_full = (int)(a.N / kTileRows);  // tiles below this one have all their rows
-        const int t1m = min(t1, last_full);            // the queue handles the full tiles [t0, t1m)
-        // A step stores the oldest tile of the queue and issues the tile kRowQueue ahead.  Tiles past the last full one
+        const int last_full = (int)(a.N / TR);  // tiles below this one have all their rows
+        const int t1m = min(t1, last_full);     // the queue handles the full tiles [t0, t1m)
+        // A step stores the oldest tile of the queue and issues the tile Q ahead.  Tiles past the last full one
         // are replaced by the last full one (loaded, never used), so that every step issues the same loads and the
         // compiler can wait for exactly the oldest tile in the queue.
-#define MAXK_TILED_ISSUE(Q, TILE)                                                                             \
+#define MAXK_TILED_ISSUE(QQ, TILE)                                                                            \
     {                                                                                                         \
         const char* const src = src0 + (int64_t)min((TILE), last_full - 1) * tile_bytes;                      \
         _Pragma("unroll") for (int rr = 0; rr < RP; ++rr)                                                     \
             _Pragma("unroll") for (int cc = 0; cc < RC; ++cc)                                                 \
                 if (col_ok[cc])                                                                               \
-                    Q[rr][cc] = *reinterpret_cast<const float4*>(src + (rr * row_bytes + cc * 1024u + lane_bytes)); \
+                    QQ[rr][cc] = *reinterpret_cast<const float4*>(src + (rr * row_bytes + cc * 1024u + lane_bytes)); \
     }
-#define MAXK_TILED_STORE(Q, TILE)                                                                             \
+#define MAXK_TILED_STORE(QQ, TILE)                                                                            \
     {                                                                                                         \
-        char* const dst = dst0 + ((TILE) & 1) * (kTileRows * row_bytes);                                      \
+        char* const dst = dst0 + ((TILE) & 1) * (TR * row_bytes);                                             \
         _Pragma("unroll") for (int rr = 0; rr < RP; ++rr)                                                     \
             _Pragma("unroll") for (int cc = 0; cc < RC; ++cc)                                                 \
-                if (col_ok[cc]) *reinterpret_cast<float4*>(dst + rr * row_bytes + cc * 1024u) = Q[rr][cc];    \
+                if (col_ok[cc]) *reinterpret_cast<float4*>(dst + rr * row_bytes + cc * 1024u) = QQ[rr][cc];   \
     }
 #pragma unroll
         for (int rr = 0; rr < RP; ++rr)
@@ -344,29 +362,35 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         if (t0 < t1m) {
             MAXK_TILED_ISSUE(q0, t0)
             MAXK_TILED_ISSUE(q1, t0 + 1)
-            MAXK_TILED_ISSUE(q2, t0 + 2)
-            MAXK_TILED_ISSUE(q3, t0 + 3)
-#define MAXK_TILED_STEP(Q, TILE) \
-    MAXK_TILED_STORE(Q, TILE)    \
-    MAXK_TILED_ISSUE(Q, (TILE) + kRowQueue) \
-    __syncthreads();
-            for (; base + kRowQueue <= t1m; base += kRowQueue) {
+            if constexpr (Q == 4) {
+                MAXK_TILED_ISSUE(q2, t0 + 2)
+                MAXK_TILED_ISSUE(q3, t0 + 3)
+            }
+#define MAXK_TILED_STEP(QQ, TILE) \
+    MAXK_TILED_STORE(QQ, TILE)    \
+    MAXK_TILED_ISSUE(QQ, (TILE) + Q) \
+    MAXK_PROF_BARRIER()
+            for (; base + Q <= t1m; base += Q) {
                 MAXK_TILED_STEP(q0, base)
                 MAXK_TILED_STEP(q1, base + 1)
-                MAXK_TILED_STEP(q2, base + 2)
-                MAXK_TILED_STEP(q3, base + 3)
+                if constexpr (Q == 4) {
+                    MAXK_TILED_STEP(q2, base + 2)
+                    MAXK_TILED_STEP(q3, base + 3)
+                }
             }
 #undef MAXK_TILED_STEP
-            if (base < t1m) { MAXK_TILED_STORE(q0, base) __syncthreads(); }
-            if (base + 1 < t1m) { MAXK_TILED_STORE(q1, base + 1) __syncthreads(); }
-            if (base + 2 < t1m) { MAXK_TILED_STORE(q2, base + 2) __syncthreads(); }
+            if (base < t1m) { MAXK_TILED_STORE(q0, base) MAXK_PROF_BARRIER() }
+            if constexpr (Q == 4) {
+                if (base + 1 < t1m) { MAXK_TILED_STORE(q1, base + 1) MAXK_PROF_BARRIER() }
+                if (base + 2 < t1m) { MAXK_TILED_STORE(q2, base + 2) MAXK_PROF_BARRIER() }
+            }
         }
         if (t1m < t1) {
             // the one tile that is cut short by the end of dY: loaded directly, row by row
             const int tile = t1m;
 #pragma unroll
             for (int rr = 0; rr < RP; ++rr) {
-                const int64_t row = (int64_t)tile * kTileRows + lw * RP + rr;
+                const int64_t row = (int64_t)tile * TR + lw * RP + rr;
 #pragma unroll
                 for (int cc = 0; cc < RC; ++cc) {
                     float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -376,7 +400,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
                 }
             }
             MAXK_TILED_STORE(q0, tile)
-            __syncthreads();
+            MAXK_PROF_BARRIER()
         }
 #undef MAXK_TILED_ISSUE
 #undef MAXK_TILED_STORE
@@ -411,8 +435,8 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         const uint32_t idx_lane = (uint32_t)q * (uint32_t)(PPL * sizeof(IdxT));
         char* const acc_lane = reinterpret_cast<char*>(acc) + q * (4 * PPL);
         const char* const rows_b = reinterpret_cast<const char*>(rows);
-        const uint32_t row_bytes = (uint32_t)dim * 4u, buf_bytes = kTileRows * row_bytes;
-        __syncthreads();  // barrier t0: the rows of tile t0 are in buffer t0 & 1
+        const uint32_t row_bytes = (uint32_t)dim * 4u, buf_bytes = TR * row_bytes;
+        MAXK_PROF_BARRIER()  // barrier t0: the rows of tile t0 are in buffer t0 & 1
 
         if (n_it > 0) {
             static_assert(kRecAhead == 8 && kIdxAhead == 4, "the queues below are written out for these depths");
@@ -458,7 +482,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         while (first + (uint32_t)(IT) * kAccWaves >= s_end) { /* next tile: everyone meets at one barrier per tile */ \
             ++tile;                                                                                                   \
             s_end = s_end_next;                                                                                       \
-            __syncthreads();                                                                                          \
+            MAXK_PROF_BARRIER()                                                                                          \
             s_end_next = *dt_next++; /* asked for after the barrier, needed at the next one */                        \
         }                                                                                                             \
         if (lane_on && !(cur.y & kVisitNull) && !(a.debug & 16)) {                                                    \
@@ -508,9 +532,12 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         }
         while (tile < t1 - 1) {
             ++tile;
-            __syncthreads();
+            MAXK_PROF_BARRIER()
         }
     }
+#ifdef MAXK_TILED_PROFILE
+    if (blockIdx.x == 8 && lane == 0 && a.prof) { a.prof[wave * 2] = clock64() - prof_start; a.prof[wave * 2 + 1] = prof_wait; }
+#endif
     __syncthreads();
     float* __restrict__ out = a.dXs + dest0 * k;
     const int n_out = Dn * k;
@@ -521,19 +548,18 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
     }
 }
 
-template <int DIMC, int RC, int PPL, typename IdxT>
+template <int TR, int DIMC, int RC, int PPL, typename IdxT>
 maxk_status launch_tiled_t(const TiledArgs& a, size_t lds_bytes, hipStream_t s)
 {
     static bool attr_set = false;  // per instantiation; the attribute is idempotent
     if (!attr_set) {
-        MAXK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_tiled_kernel<DIMC, RC, PPL, IdxT>),
+        MAXK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_tiled_kernel<TR, DIMC, RC, PPL, IdxT>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
         attr_set = true;
     }
-    const int rounds = (a.R + a.C - 1) / a.C;
-    const int64_t grid = (int64_t)8 * a.C * a.G * rounds;
+    const int64_t grid = (int64_t)8 * a.G * a.R;
     if (grid > 0x7FFFFFFFll) return MAXK_UNSUPPORTED;
-    hipLaunchKernelGGL((bwd_tiled_kernel<DIMC, RC, PPL, IdxT>), dim3((unsigned)grid), dim3(kTiledThreads), lds_bytes, s, a);
+    hipLaunchKernelGGL((bwd_tiled_kernel<TR, DIMC, RC, PPL, IdxT>), dim3((unsigned)grid), dim3(kTiledThreads), lds_bytes, s, a);
     MAXK_LAUNCH_CHECK();
     return MAXK_OK;
 }
@@ -553,27 +579,39 @@ void free_tiled(TiledSet& T)
     T = TiledSet();
 }
 
-bool tiled_shape(int64_t N, int dim, int k, int& D, int& n_dsets)
+// Tile height and destination-set size for (N, dim, k).  tr_knob / d_knob: 0, or the value to use (tuning knobs).
+bool tiled_shape(int64_t N, int dim, int k, int tr_knob, int d_knob, TiledShape& sh)
 {
     if (N < 1 || k % 4 != 0 || k < 4 || k > 256 || dim % 4 != 0 || dim > 512) return false;
-    const int64_t row_bytes = 2ll * kTileRows * dim * 4;
+    int tr = 16;
+    if (dim == 256 && (tr_knob == 32 || tr_knob == 48)) tr = tr_knob;  // taller tiles are compiled for width 256 only
+    const int64_t row_bytes = 2ll * tr * dim * 4;
     const int64_t dmax = std::min<int64_t>((kLdsBytes - row_bytes - 256) / (4ll * k), 4096);
     if (dmax < 64) return false;
-    int64_t S = 8;
-    while ((N + S - 1) / S > dmax) S *= 2;
-    if (S > 65536) return false;
-    D = (int)((N + S - 1) / S);
-    n_dsets = (int)((N + D - 1) / D);
+    int64_t D;
+    if (d_knob > 0) {
+        D = std::min<int64_t>(d_knob, dmax);
+    } else {
+        int64_t S = 8;  // a power of two of sets: the 32 CUs of an XCD then hold whole groups of them
+        while ((N + S - 1) / S > dmax) S *= 2;
+        D = (N + S - 1) / S;
+    }
+    D = std::max<int64_t>(D, 1);
+    const int64_t n_dsets = (N + D - 1) / D;
+    if (n_dsets > 65536) return false;
+    sh.D = (int)D;
+    sh.TR = tr;
+    sh.n_dsets = (int)n_dsets;
     return true;
 }
 
 // Builds the visit lists for destination sets of D nodes and k/4 lanes per visit.  Synchronises the device.
 maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_csc_ptr, const int32_t* d_csc_src,
-                        const float* d_csc_val, int D, int k)
+                        const float* d_csc_val, int D, int TR, int k)
 {
     const int LPV = k / tiled_positions_per_lane(k), E = kWave / LPV;
     MAXK_HIP_TRY(hipDeviceSynchronize());
-    const int64_t n_dsets = (N + D - 1) / D, n_tiles = (N + kTileRows - 1) / kTileRows;
+    const int64_t n_dsets = (N + D - 1) / D, n_tiles = (N + TR - 1) / TR;
     const int64_t n_groups = n_dsets * n_tiles;
     if (n_groups + 1 > ((int64_t)1 << 28) || nnz < 1 || (int64_t)D * LPV > (int64_t)kVisitAccMask + 1) return MAXK_UNSUPPORTED;
     hipStream_t s = nullptr;
@@ -596,8 +634,8 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_key, sizeof(uint64_t) * (size_t)nnz));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_key_sorted, sizeof(uint64_t) * (size_t)nnz));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_val_sorted, sizeof(float) * (size_t)nnz));
-    hipLaunchKernelGGL(tiled_keys_kernel, dim3(blocks), dim3(256), 0, s, d_csc_ptr, d_csc_src, N, nnz, D, (int32_t)n_tiles,
-                       d_key);
+    hipLaunchKernelGGL(tiled_keys_kernel, dim3(blocks), dim3(256), 0, s, d_csc_ptr, d_csc_src, N, nnz, D, TR,
+                       (int32_t)n_tiles, d_key);
     MAXK_TRY_CLEAN(hipGetLastError());
     int end_bit = 19;
     while (end_bit < 64 && ((uint64_t)1 << (end_bit - 18)) < (uint64_t)n_groups) ++end_bit;
@@ -669,6 +707,7 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
 #undef MAXK_TRY_CLEAN
     cleanup();
     T.D = D;
+    T.TR = TR;
     T.E = E;
     T.LPV = LPV;
     T.n_dsets = (int32_t)n_dsets;
@@ -703,33 +742,57 @@ maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, 
     a.D = T.D;
     a.n_dsets = T.n_dsets;
     a.n_tiles = T.n_tiles;
-    // destination sets per XCD, and how many source ranges the 32 CUs of an XCD work on at a time
+    // An XCD holds G destination sets and runs 32 workgroups at a time; the source rows are cut into R ranges so that
+    // its G * R units fill whole rounds of 32 (as nearly as a small R allows).
     a.G = (T.n_dsets + 7) / 8;
-    a.C = std::max(1, 32 / a.G);
-    a.R = std::min<int>(a.C, std::max<int>(1, T.n_tiles / 8));
+    int best_r = 1;
+    double best_fill = 0.0;
+    for (int r = 1; r <= 32; ++r) {
+        const int units = a.G * r;
+        const double fill = (double)units / (32.0 * ((units + 31) / 32));
+        if (fill > best_fill + 0.02) { best_fill = fill; best_r = r; }
+    }
+    a.R = std::min<int>(best_r, std::max<int>(1, T.n_tiles / 8));
     a.tiles_per_range = (T.n_tiles + a.R - 1) / a.R;
     a.R = (T.n_tiles + a.tiles_per_range - 1) / a.tiles_per_range;
     a.atomic_out = a.R > 1;
     a.debug = getenv("MAXK_TILED_DEBUG") ? atoi(getenv("MAXK_TILED_DEBUG")) : 0;
+    a.prof = nullptr;
+#ifdef MAXK_TILED_PROFILE
+    static long long* d_prof = nullptr;
+    if (!d_prof) (void)hipMalloc((void**)&d_prof, 64 * sizeof(long long));
+    (void)hipMemset(d_prof, 0, 64 * sizeof(long long));
+    a.prof = d_prof;
+#endif
     if (a.atomic_out) {
         const maxk_status st = launch_fill_zero(dXs, N * (int64_t)k, s);
         if (st != MAXK_OK) return st;
     }
-    const size_t lds_bytes = sizeof(float) * ((size_t)((T.D * k + 3) & ~3) + 2 * (size_t)kTileRows * dim);
+    const size_t lds_bytes = sizeof(float) * ((size_t)((T.D * k + 3) & ~3) + 2 * (size_t)T.TR * dim);
     if (lds_bytes > (size_t)kLdsBytes) return MAXK_UNSUPPORTED;
-#define MAXK_TILED_I(DIMC, RC, PPL)                                                                               \
-    (index_bytes == 1 ? launch_tiled_t<DIMC, RC, PPL, uint8_t>(a, lds_bytes, s)                                   \
-     : index_bytes == 2 ? launch_tiled_t<DIMC, RC, PPL, uint16_t>(a, lds_bytes, s)                                \
-                        : launch_tiled_t<DIMC, RC, PPL, int32_t>(a, lds_bytes, s))
+#define MAXK_TILED_I(TR, DIMC, RC, PPL)                                                                           \
+    (index_bytes == 1 ? launch_tiled_t<TR, DIMC, RC, PPL, uint8_t>(a, lds_bytes, s)                               \
+     : index_bytes == 2 ? launch_tiled_t<TR, DIMC, RC, PPL, uint16_t>(a, lds_bytes, s)                            \
+                        : launch_tiled_t<TR, DIMC, RC, PPL, int32_t>(a, lds_bytes, s))
+    maxk_status st;
     if (tiled_positions_per_lane(k) == 8) {
-        if (dim == 256) return MAXK_TILED_I(256, 1, 8);
-        if (dim < 256) return MAXK_TILED_I(0, 1, 8);
-        return MAXK_TILED_I(0, 2, 8);
+        if (dim == 256) st = T.TR == 48 ? MAXK_TILED_I(48, 256, 1, 8) : T.TR == 32 ? MAXK_TILED_I(32, 256, 1, 8) : MAXK_TILED_I(16, 256, 1, 8);
+        else st = dim < 256 ? MAXK_TILED_I(16, 0, 1, 8) : MAXK_TILED_I(16, 0, 2, 8);
+    } else {
+        if (dim == 256) st = T.TR == 48 ? MAXK_TILED_I(48, 256, 1, 4) : T.TR == 32 ? MAXK_TILED_I(32, 256, 1, 4) : MAXK_TILED_I(16, 256, 1, 4);
+        else st = dim < 256 ? MAXK_TILED_I(16, 0, 1, 4) : MAXK_TILED_I(16, 0, 2, 4);
     }
-    if (dim == 256) return MAXK_TILED_I(256, 1, 4);
-    if (dim < 256) return MAXK_TILED_I(0, 1, 4);
-    return MAXK_TILED_I(0, 2, 4);
 #undef MAXK_TILED_I
+#ifdef MAXK_TILED_PROFILE
+    if (getenv("MAXK_TILED_PROFILE_PRINT")) {
+        long long h[32];
+        (void)hipDeviceSynchronize();
+        (void)hipMemcpy(h, a.prof, sizeof(h), hipMemcpyDeviceToHost);
+        fprintf(stderr, "tiled profile (block 8; per wavefront: total clocks, clocks inside barriers):\n");
+        for (int w = 0; w < kAccWaves + kLoadWaves + 1; ++w) fprintf(stderr, "  wave %2d: %lld %lld\n", w, h[2 * w], h[2 * w + 1]);
+    }
+#endif
+    return st;
 }
 
 }  // namespace maxk
