@@ -49,7 +49,8 @@ enum {
     MAXK_INVALID_ARGUMENT = -1, /* null pointer, negative size, k outside [1,dim], bad index_bytes, misaligned pointer */
     MAXK_UNSUPPORTED = -2,      /* dim above MAXK_MAX_DIM */
     MAXK_HIP_ERROR = -3,        /* a HIP call failed; see maxk_last_hip_error() */
-    MAXK_OUT_OF_MEMORY = -4
+    MAXK_OUT_OF_MEMORY = -4,
+    MAXK_SCRATCH_TOO_SMALL = -5 /* maxk_spgemm_fwd_noalloc: the graph's split rows need more than the fixed array */
 };
 
 /* Largest hidden width the kernels are compiled for. */
@@ -140,6 +141,23 @@ MAXK_API maxk_status maxk_topk_cbsr(const float* d_H, int64_t N, int32_t dim, in
  */
 MAXK_API maxk_status maxk_spgemm_fwd(maxk_graph* g, const float* d_sp_data, const void* d_sp_index, int32_t index_bytes,
                             int32_t dim, int32_t k, float* d_Y, void* stream);
+
+/*
+ * maxk_spgemm_fwd for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same result.  The forward kernels' scratch memory -- the partial rows
+ * of rows that were split over several work items (slots x dim floats), and the per-call repack of a small-k
+ * CBSR -- lives in a fixed array of MAXK_NOALLOC_SCRATCH_BYTES inside the library's device image instead of the
+ * handle's workspaces, so this call never calls hipMalloc, hipFree or any allocating routine, whatever was or was
+ * not reserved.  Every GPU holds its own copy of the array from the moment the library is loaded there until the
+ * process ends.  MAXK_SCRATCH_TOO_SMALL when the split rows alone need more than the array (nothing is launched);
+ * when only the repacked CBSR does not fit, the kernel reads sp_data / sp_index directly (same result, slower at
+ * small k).  Must be called with the device current on which the handle was created.  All calls on one GPU share
+ * the array, on any handle and any stream: calls that overlap in time on one GPU race; order them on one stream
+ * or with events.  Nothing in the array needs clearing between calls.
+ */
+#define MAXK_NOALLOC_SCRATCH_BYTES (32u << 20)
+MAXK_API maxk_status maxk_spgemm_fwd_noalloc(maxk_graph* g, const float* d_sp_data, const void* d_sp_index,
+                                             int32_t index_bytes, int32_t dim, int32_t k, float* d_Y, void* stream);
 
 /*
  * The same two steps with the CBSR values stored in 2 bytes (value_type MAXK_VALUE_BF16 or _F16;

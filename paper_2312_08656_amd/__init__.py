@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     maxk_graph_destroy,
     maxk_spgemm_fwd,
     maxk_spgemm_fwd_narrow,
+    maxk_spgemm_fwd_noalloc,
     maxk_sspmm_bwd,
     maxk_sspmm_bwd_narrow,
     maxk_topk_cbsr,

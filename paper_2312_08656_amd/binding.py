@@ -17,7 +17,7 @@ EXPORTS = (
     "maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_reserve_narrow",
     "maxk_graph_set_bwd_mode", "maxk_graph_bwd_choice",
     "maxk_graph_info",
-    "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_topk_cbsr_narrow", "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd",
+    "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_spgemm_fwd_noalloc", "maxk_topk_cbsr_narrow", "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd",
     "maxk_sspmm_bwd_narrow", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
     "maxk_last_hip_error", "maxk_version", "maxk_fwd_private_copies",
 )
@@ -51,6 +51,7 @@ def load_library() -> ctypes.CDLL:
     lib.maxk_graph_info.argtypes = [vp] + [ctypes.POINTER(i64)] * 6
     lib.maxk_topk_cbsr.argtypes = [vp, i64, i32, i32, vp, vp, i32, vp]
     lib.maxk_spgemm_fwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.maxk_spgemm_fwd_noalloc.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     lib.maxk_topk_cbsr_narrow.argtypes = [vp, i64, i32, i32, vp, i32, vp, i32, vp]
     lib.maxk_spgemm_fwd_narrow.argtypes = [vp, vp, i32, vp, i32, i32, i32, vp, vp]
     lib.maxk_sspmm_bwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
@@ -59,7 +60,7 @@ def load_library() -> ctypes.CDLL:
     lib.spmm_baseline.argtypes = [vp, vp, i32, vp, vp]
     for name in ("maxk_graph_create", "maxk_graph_destroy", "maxk_graph_reserve", "maxk_graph_reserve_narrow",
                  "maxk_graph_set_bwd_mode",
-                 "maxk_graph_info", "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_topk_cbsr_narrow",
+                 "maxk_graph_info", "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_spgemm_fwd_noalloc", "maxk_topk_cbsr_narrow",
                  "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd", "maxk_sspmm_bwd_narrow", "maxk_cbsr_scatter",
                  "spmm_baseline",
                  "maxk_last_hip_error", "maxk_version"):
@@ -182,6 +183,18 @@ def maxk_spgemm_fwd(g: MaxKGraph, sp_data: torch.Tensor, sp_index: torch.Tensor,
     _check(load_library().maxk_spgemm_fwd(g.handle, _dev(sp_data, torch.float32, "sp_data"),
                                           _dev(sp_index, sp_index.dtype, "sp_index"), ib, dim, k,
                                           _dev(Y, torch.float32, "Y"), _stream()), "maxk_spgemm_fwd")
+
+
+def maxk_spgemm_fwd_noalloc(g: MaxKGraph, sp_data: torch.Tensor, sp_index: torch.Tensor, dim: int,
+                            Y: torch.Tensor) -> None:
+    """maxk_spgemm_fwd with its scratch memory in the library's fixed device array: allocates nothing."""
+    N, k = sp_data.shape
+    if N != g.N or tuple(sp_index.shape) != (N, k) or tuple(Y.shape) != (N, dim):
+        raise MaxKError("maxk_spgemm_fwd_noalloc: shape mismatch")
+    ib = _INDEX_BYTES[sp_index.dtype]
+    _check(load_library().maxk_spgemm_fwd_noalloc(g.handle, _dev(sp_data, torch.float32, "sp_data"),
+                                                  _dev(sp_index, sp_index.dtype, "sp_index"), ib, dim, k,
+                                                  _dev(Y, torch.float32, "Y"), _stream()), "maxk_spgemm_fwd_noalloc")
 
 
 def maxk_topk_cbsr_narrow(H: torch.Tensor, k: int, sp_data: torch.Tensor, sp_index: torch.Tensor) -> None:

@@ -29,8 +29,7 @@ def build(verbose: bool = False) -> Path:
 
     def compile_one(src: str) -> Path:
         obj = objdir / (src + ".o")
-        extra = os.environ.get("MAXK_EXTRA_HIPCC_FLAGS", "").split()  # e.g. instrumentation switches, for experiments
-        cmd = [hipcc, *HIPCC_FLAGS, *extra, "-c", str(CSRC / src), "-o", str(obj)]
+        cmd = [hipcc, *HIPCC_FLAGS, "-c", str(CSRC / src), "-o", str(obj)]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

@@ -166,7 +166,7 @@ maxk_status launch_bwd_slab_pull(const SlabSet& S, const void* dY, int value_typ
 
 // LDS-tiled backward kernel (fp32 dY, k % 4 == 0, dim % 4 == 0, dim <= 512)
 struct TiledShape { int D = 0, TR = 0, n_dsets = 0; };
-bool tiled_shape(int64_t N, int dim, int k, int tr_knob, int d_knob, TiledShape& sh);  // false: (N, dim, k) not supported
+bool tiled_shape(int64_t N, int dim, int k, TiledShape& sh);  // false: (N, dim, k) not supported
 int tiled_positions_per_lane(int k);
 bool tiled_supports(const void* dY, int value_type, const void* sp_index, int index_bytes, int dim, int k);
 maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_csc_ptr, const int32_t* d_csc_src,

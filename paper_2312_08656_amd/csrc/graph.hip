@@ -45,15 +45,28 @@ struct maxk_graph {
     int32_t chunk = 0;         // tuning knobs, read from the environment once, by maxk_graph_create
     int32_t slab_kb = 0;
     int32_t fwd_pack_max = 0;
-    int32_t tiled_tr = 0, tiled_d = 0;  // 0: the library's choice
+    unsigned char* d_noalloc_scratch = nullptr;  // this device's copy of the library's fixed scratch array
     int device = 0;
 };
+
+// Scratch memory of maxk_spgemm_fwd_noalloc: a fixed array in the library's device image, one copy per GPU, alive
+// until the process ends.  In host code this name is a handle for hipGetSymbolAddress only, never a pointer.
+static __device__ __align__(256) unsigned char maxk_noalloc_scratch[MAXK_NOALLOC_SCRATCH_BYTES];
 
 namespace maxk {
 
 thread_local int32_t g_last_hip_error = 0;
 
 namespace {
+
+// Device address of the scratch array on the current device (asked for once per handle, by maxk_graph_create).
+maxk_status noalloc_scratch_address(unsigned char** out)
+{
+    void* p = nullptr;
+    MAXK_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(maxk_noalloc_scratch)));
+    *out = static_cast<unsigned char*>(p);
+    return p ? MAXK_OK : MAXK_HIP_ERROR;
+}
 
 int env_int(const char* name, int dflt, int lo, int hi)
 {
@@ -459,7 +472,7 @@ maxk_status slabs_for(maxk_graph* g, int32_t slab_rows, SlabSet** out)
 maxk_status tiled_for(maxk_graph* g, int dim, int k, TiledSet** out)
 {
     TiledShape sh;
-    if (!tiled_shape(g->N, dim, k, g->tiled_tr, g->tiled_d, sh)) return MAXK_UNSUPPORTED;
+    if (!tiled_shape(g->N, dim, k, sh)) return MAXK_UNSUPPORTED;
     for (TiledSet* T : g->tiled_cache)
         if (T->D == sh.D && T->TR == sh.TR && T->LPV == k / tiled_positions_per_lane(k)) { *out = T; return MAXK_OK; }
     TiledSet* T = new (std::nothrow) TiledSet();
@@ -514,21 +527,26 @@ maxk_status ensure_expand(maxk_graph* g, int k)
 // min(k, dim/32) cache lines of a dY row per entry whatever k is, so pull wins once k is large.
 int auto_bwd_mode(const maxk_graph* g, int dim, int k, int val_bytes = 4, bool tiled_ok = true)
 {
-    // LDS-tiled: a workgroup's wavefront gets nnz * 16 * D / (4 N^2) visits per tile; it pays off once those fill
-    // a good part of a wave instruction (64 / (k/4) visits)
-    TiledShape sh;
-    if (tiled_ok && val_bytes == 4 && g->nnz > 0 && tiled_shape(g->N, dim, k, g->tiled_tr, g->tiled_d, sh)) {
-        const double per_tile = (double)g->nnz * sh.TR * sh.D / ((double)g->N * (double)g->N);  // visits per tile
-        const double n_lists = (double)sh.n_dsets * std::ceil((double)g->N / sh.TR);
-        if (per_tile >= 1.6 * (64.0 / (k / tiled_positions_per_lane(k))) && n_lists < 2.6e8) return MAXK_BWD_TILED;
-    }
     const double n_slabs = std::ceil((double)g->N / slab_rows_for(g, dim, val_bytes));
     const double entries_per_visit = (double)g->nnz / std::max(1.0, (double)g->N * n_slabs);
-    if (entries_per_visit >= 2.0 && n_slabs * (double)g->N < 1.8e19) return MAXK_BWD_SLAB_PULL;
-    // expected cache lines of a dY row touched by k sorted columns; measured crossover on four graphs:
-    // expand/reduce (8k bytes per entry) beats pull (lines * 128 bytes per entry) while 8k < 44 * lines
     const double per_line = 128.0 / val_bytes;  // dY elements per cache line
     const double lines = dim <= per_line ? 1.0 : (dim / per_line) * (1.0 - std::pow(1.0 - per_line / dim, (double)k));
+    if (entries_per_visit >= 2.0 && n_slabs * (double)g->N < 1.8e19) {
+        // Dense neighbourhoods: slab pull or the LDS-tiled kernel, by cost models fitted on the dense workload (256 CUs):
+        // slab pull moves the cache lines that an entry's k columns touch (plus ~0.35 lines of streamed arrays) at
+        // ~5.6 ps per line, and pays ~10 us per slab launch; the tiled kernel pays ~270 ns per (destination set,
+        // tile) step on each CU and ~(7.1 + 0.41 k) ps per entry.
+        TiledShape sh;
+        if (tiled_ok && val_bytes == 4 && tiled_shape(g->N, dim, k, sh)) {
+            const double n_tiles = std::ceil((double)g->N / sh.TR);
+            const double t_slab = (double)g->nnz * (lines + 0.35) * 5.6e-12 + n_slabs * 10e-6;
+            const double t_tiled = 270e-9 * sh.n_dsets * n_tiles / 256.0 + (double)g->nnz * (7.1e-12 + 0.41e-12 * k);
+            if (t_tiled < t_slab && (double)sh.n_dsets * n_tiles < 2.6e8) return MAXK_BWD_TILED;
+        }
+        return MAXK_BWD_SLAB_PULL;
+    }
+    // `lines`: expected cache lines of a dY row touched by k sorted columns; measured crossover on four graphs:
+    // expand/reduce (8k bytes per entry) beats pull (lines * 128 bytes per entry) while 8k < 44 * lines
     const double pull_cost = lines * 128.0 / 2.9;
     const double expand_cost = 8.0 * k;
     const bool fits = (double)g->nnz * k * 4.0 <= 96e9;
@@ -569,9 +587,11 @@ MAXK_API maxk_status maxk_graph_create(maxk_graph** out, int64_t N, int64_t nnz,
     g->chunk = env_int("MAXK_CHUNK", 2048, 64, 1 << 20);  // measured plateau: 2048 and up
     g->slab_kb = env_int("MAXK_SLAB_KB", 3584, 64, 1 << 20);
     g->fwd_pack_max = env_int("MAXK_FWD_PACK_MAX", 96, 0, 1 << 20);
-    g->tiled_tr = env_int("MAXK_TILED_ROWS", 0, 0, 64);
-    g->tiled_d = env_int("MAXK_TILED_DESTS", 0, 0, 4096);
     (void)hipGetDevice(&g->device);
+    {
+        const maxk_status sst = noalloc_scratch_address(&g->d_noalloc_scratch);
+        if (sst != MAXK_OK) { delete g; return sst; }
+    }
 
     maxk_status st = MAXK_OK;
     try {
@@ -745,6 +765,30 @@ MAXK_API maxk_status maxk_spgemm_fwd(maxk_graph* g, const float* d_sp_data, cons
     return maxk_spgemm_fwd_narrow(g, d_sp_data, MAXK_VALUE_F32, d_sp_index, index_bytes, dim, k, d_Y, stream);
 }
 
+MAXK_API maxk_status maxk_spgemm_fwd_noalloc(maxk_graph* g, const float* d_sp_data, const void* d_sp_index,
+                                             int32_t index_bytes, int32_t dim, int32_t k, float* d_Y, void* stream)
+{
+    if (!g || dim < 1 || k < 1 || k > dim || bad_index_bytes(index_bytes, dim)) return MAXK_INVALID_ARGUMENT;
+    if (dim > MAXK_MAX_DIM) return MAXK_UNSUPPORTED;
+    if (g->N == 0) return MAXK_OK;
+    if (!d_sp_data || !d_sp_index || !d_Y) return MAXK_INVALID_ARGUMENT;
+    if (!aligned(d_sp_data, 4) || !aligned(d_Y, 4) || !aligned(d_sp_index, (size_t)index_bytes)) return MAXK_INVALID_ARGUMENT;
+    int device = -1;
+    MAXK_HIP_TRY(hipGetDevice(&device));
+    if (device != g->device || !g->d_noalloc_scratch) return MAXK_INVALID_ARGUMENT;  // the array is per GPU
+    // layout of the scratch array: [partial rows of split rows | repacked CBSR, if it fits]
+    const int64_t partial_bytes = (g->csr_items.n_slots * (int64_t)dim * 4 + 255) & ~(int64_t)255;
+    if (partial_bytes > (int64_t)MAXK_NOALLOC_SCRATCH_BYTES) return MAXK_SCRATCH_TOO_SMALL;
+    float* partials = reinterpret_cast<float*>(g->d_noalloc_scratch);
+    char* packed = nullptr;
+    if (fwd_uses_packed(g, k, index_bytes, 4) &&
+        partial_bytes + g->N * (int64_t)fwd_packed_record_bytes(k, index_bytes, 4) <= (int64_t)MAXK_NOALLOC_SCRATCH_BYTES)
+        packed = reinterpret_cast<char*>(g->d_noalloc_scratch) + partial_bytes;
+    // nothing in the array has to start at zero: the kernels write every partial row and every record they read
+    return launch_spgemm_fwd(g->csr_items, g->d_col, g->d_val, d_sp_data, MAXK_VALUE_F32, d_sp_index, index_bytes, g->N,
+                             packed, dim, k, d_Y, partials, (hipStream_t)stream);
+}
+
 MAXK_API maxk_status maxk_sspmm_bwd_narrow(maxk_graph* g, const void* d_dY, int32_t value_type, const void* d_sp_index,
                                            int32_t index_bytes, int32_t dim, int32_t k, float* d_dXs, void* stream)
 {
@@ -828,6 +872,7 @@ MAXK_API const char* maxk_status_string(maxk_status s)
         case MAXK_UNSUPPORTED: return "unsupported size";
         case MAXK_HIP_ERROR: return "HIP runtime error";
         case MAXK_OUT_OF_MEMORY: return "out of device or host memory";
+        case MAXK_SCRATCH_TOO_SMALL: return "the input needs more scratch memory than the library's fixed array holds";
         default: return "unknown status";
     }
 }

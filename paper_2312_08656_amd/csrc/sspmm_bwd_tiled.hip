@@ -36,13 +36,6 @@
 
 #include "common.hpp"
 
-#ifdef MAXK_TILED_PROFILE
-#include <cstdio>
-#define MAXK_PROF_BARRIER() { const long long _t0 = clock64(); __syncthreads(); prof_wait += clock64() - _t0; }
-#else
-#define MAXK_PROF_BARRIER() __syncthreads();
-#endif
-
 namespace maxk {
 namespace {
 
@@ -187,8 +180,6 @@ struct TiledArgs {
     int32_t D, n_dsets, n_tiles;
     int32_t G, R, tiles_per_range;  // destination sets per XCD, source ranges, tiles per range
     int32_t atomic_out;
-    int32_t debug;
-    long long* prof;
 };
 
 // PPL (4 or 8) consecutive sp_index entries, fetched with as few loads as their width allows
@@ -281,10 +272,6 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
     // Barrier protocol: barrier number t (t = t0 .. t1-1) is passed by the loaders after they have written tile t and
     // by the accumulators before they start on tile t, i.e. after they have finished tile t-1.  Every wavefront
     // executes exactly t1 - t0 of them, whatever its role.
-#ifdef MAXK_TILED_PROFILE
-    long long prof_wait = 0;
-    const long long prof_start = clock64();
-#endif
     if (wave == kAccWaves + kLoadWaves) {
         // ---- prefetching wavefront ----
         // The workgroups of an XCD that sweep one source range move as a pack: whoever is first takes the miss to
@@ -297,7 +284,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         const int pack = min(a.G, 32);  // workgroups that share the lines of a round
         const int64_t row_bytes = (int64_t)dim * 4, total_bytes = a.N * row_bytes;
         const int64_t lines_per_group = (PG * TR * row_bytes + 127) / 128;
-        const int pf_loads = (pack >= 8 && !(a.debug & 4)) ? (int)min((int64_t)4, (lines_per_group / pack + kWave - 1) / kWave) : 0;
+        const int pf_loads = pack >= 8 ? (int)min((int64_t)4, (lines_per_group / pack + kWave - 1) / kWave) : 0;
         uint32_t got[4] = {0u, 0u, 0u, 0u};
         int countdown = 0;
         for (int tile = t0; tile < t1; ++tile) {
@@ -314,7 +301,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
                 countdown = PG;
             }
             --countdown;
-            MAXK_PROF_BARRIER()
+            __syncthreads();
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(got[j]));
@@ -369,7 +356,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
 #define MAXK_TILED_STEP(QQ, TILE) \
     MAXK_TILED_STORE(QQ, TILE)    \
     MAXK_TILED_ISSUE(QQ, (TILE) + Q) \
-    MAXK_PROF_BARRIER()
+    __syncthreads();
             for (; base + Q <= t1m; base += Q) {
                 MAXK_TILED_STEP(q0, base)
                 MAXK_TILED_STEP(q1, base + 1)
@@ -379,10 +366,10 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
                 }
             }
 #undef MAXK_TILED_STEP
-            if (base < t1m) { MAXK_TILED_STORE(q0, base) MAXK_PROF_BARRIER() }
+            if (base < t1m) { MAXK_TILED_STORE(q0, base) __syncthreads(); }
             if constexpr (Q == 4) {
-                if (base + 1 < t1m) { MAXK_TILED_STORE(q1, base + 1) MAXK_PROF_BARRIER() }
-                if (base + 2 < t1m) { MAXK_TILED_STORE(q2, base + 2) MAXK_PROF_BARRIER() }
+                if (base + 1 < t1m) { MAXK_TILED_STORE(q1, base + 1) __syncthreads(); }
+                if (base + 2 < t1m) { MAXK_TILED_STORE(q2, base + 2) __syncthreads(); }
             }
         }
         if (t1m < t1) {
@@ -400,7 +387,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
                 }
             }
             MAXK_TILED_STORE(q0, tile)
-            MAXK_PROF_BARRIER()
+            __syncthreads();
         }
 #undef MAXK_TILED_ISSUE
 #undef MAXK_TILED_STORE
@@ -420,7 +407,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         // first + 8 i, i = 0 .. n_it - 1
         const uint32_t u0 = dt[t0], u1 = dt[t1];
         const uint32_t first = u0 + (((uint32_t)wave - u0) & (uint32_t)(kAccWaves - 1));
-        const int n_it = ((a.debug & 2) || first >= u1) ? 0 : (int)((u1 - first + kAccWaves - 1) / kAccWaves);
+        const int n_it = first >= u1 ? 0 : (int)((u1 - first + kAccWaves - 1) / kAccWaves);
         int tile = t0;
         uint32_t s_end = dt[t0 + 1];                 // first set past `tile`
         uint32_t s_end_next = dt[t0 + 2];            // (the directory has two spare entries at its end)
@@ -436,7 +423,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         char* const acc_lane = reinterpret_cast<char*>(acc) + q * (4 * PPL);
         const char* const rows_b = reinterpret_cast<const char*>(rows);
         const uint32_t row_bytes = (uint32_t)dim * 4u, buf_bytes = TR * row_bytes;
-        MAXK_PROF_BARRIER()  // barrier t0: the rows of tile t0 are in buffer t0 & 1
+        __syncthreads();  // barrier t0: the rows of tile t0 are in buffer t0 & 1
 
         if (n_it > 0) {
             static_assert(kRecAhead == 8 && kIdxAhead == 4, "the queues below are written out for these depths");
@@ -482,10 +469,10 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         while (first + (uint32_t)(IT) * kAccWaves >= s_end) { /* next tile: everyone meets at one barrier per tile */ \
             ++tile;                                                                                                   \
             s_end = s_end_next;                                                                                       \
-            MAXK_PROF_BARRIER()                                                                                          \
+            __syncthreads();                                                                                          \
             s_end_next = *dt_next++; /* asked for after the barrier, needed at the next one */                        \
         }                                                                                                             \
-        if (lane_on && !(cur.y & kVisitNull) && !(a.debug & 16)) {                                                    \
+        if (lane_on && !(cur.y & kVisitNull)) {                                                                       \
             const char* const buf = rows_b + (tile & 1) * buf_bytes;                                                  \
             float4* const ap = reinterpret_cast<float4*>(acc_lane + (cur.y & kVisitAccMask) * (uint32_t)(4 * PPL));   \
             float4 av[NQ];                                                                                            \
@@ -532,12 +519,9 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         }
         while (tile < t1 - 1) {
             ++tile;
-            MAXK_PROF_BARRIER()
+            __syncthreads();
         }
     }
-#ifdef MAXK_TILED_PROFILE
-    if (blockIdx.x == 8 && lane == 0 && a.prof) { a.prof[wave * 2] = clock64() - prof_start; a.prof[wave * 2 + 1] = prof_wait; }
-#endif
     __syncthreads();
     float* __restrict__ out = a.dXs + dest0 * k;
     const int n_out = Dn * k;
@@ -566,9 +550,10 @@ maxk_status launch_tiled_t(const TiledArgs& a, size_t lds_bytes, hipStream_t s)
 
 }  // namespace
 
-// CBSR positions one lane works on: 8 where k allows, so that a wave instruction (and the loads that feed it)
-// covers twice as many visits
-int tiled_positions_per_lane(int k) { return k % 8 == 0 ? 8 : 4; }
+// CBSR positions one lane works on.  Eight (where k allows) were measured no faster than four on the dense workload
+// (2.20 / 3.82 / 7.3 ms against 2.17 / 3.54 / 6.65 ms at k = 8 / 16 / 32): half as many wave instructions, each
+// nearly twice as long.
+int tiled_positions_per_lane(int) { return 4; }
 
 void free_tiled(TiledSet& T)
 {
@@ -579,24 +564,19 @@ void free_tiled(TiledSet& T)
     T = TiledSet();
 }
 
-// Tile height and destination-set size for (N, dim, k).  tr_knob / d_knob: 0, or the value to use (tuning knobs).
-bool tiled_shape(int64_t N, int dim, int k, int tr_knob, int d_knob, TiledShape& sh)
+// Destination-set size for (N, dim, k): as many nodes as LDS holds accumulators for beside two row buffers, rounded
+// so that the number of sets is a power of two (the 32 CUs of an XCD then hold whole groups of sets).  Tiles of 16
+// rows: taller ones (32, 48 rows, with correspondingly smaller sets) were measured slower at every k.
+bool tiled_shape(int64_t N, int dim, int k, TiledShape& sh)
 {
     if (N < 1 || k % 4 != 0 || k < 4 || k > 256 || dim % 4 != 0 || dim > 512) return false;
-    int tr = 16;
-    if (dim == 256 && (tr_knob == 32 || tr_knob == 48)) tr = tr_knob;  // taller tiles are compiled for width 256 only
+    const int tr = 16;
     const int64_t row_bytes = 2ll * tr * dim * 4;
     const int64_t dmax = std::min<int64_t>((kLdsBytes - row_bytes - 256) / (4ll * k), 4096);
     if (dmax < 64) return false;
-    int64_t D;
-    if (d_knob > 0) {
-        D = std::min<int64_t>(d_knob, dmax);
-    } else {
-        int64_t S = 8;  // a power of two of sets: the 32 CUs of an XCD then hold whole groups of them
-        while ((N + S - 1) / S > dmax) S *= 2;
-        D = (N + S - 1) / S;
-    }
-    D = std::max<int64_t>(D, 1);
+    int64_t S = 8;
+    while ((N + S - 1) / S > dmax) S *= 2;
+    const int64_t D = (N + S - 1) / S;
     const int64_t n_dsets = (N + D - 1) / D;
     if (n_dsets > 65536) return false;
     sh.D = (int)D;
@@ -727,7 +707,7 @@ bool tiled_supports(const void* dY, int value_type, const void* sp_index, int in
 maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, const void* sp_index, int index_bytes,
                              int64_t N, int dim, int k, float* dXs, hipStream_t s)
 {
-    if (!tiled_supports(dY, value_type, sp_index, index_bytes, dim, k) || T.LPV != k / tiled_positions_per_lane(k)) return MAXK_UNSUPPORTED;
+    if (!tiled_supports(dY, value_type, sp_index, index_bytes, dim, k) || T.LPV != k / tiled_positions_per_lane(k) || T.TR != 16) return MAXK_UNSUPPORTED;
     TiledArgs a;
     a.dY = (const float*)dY;
     a.sp_index = sp_index;
@@ -756,14 +736,6 @@ maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, 
     a.tiles_per_range = (T.n_tiles + a.R - 1) / a.R;
     a.R = (T.n_tiles + a.tiles_per_range - 1) / a.tiles_per_range;
     a.atomic_out = a.R > 1;
-    a.debug = getenv("MAXK_TILED_DEBUG") ? atoi(getenv("MAXK_TILED_DEBUG")) : 0;
-    a.prof = nullptr;
-#ifdef MAXK_TILED_PROFILE
-    static long long* d_prof = nullptr;
-    if (!d_prof) (void)hipMalloc((void**)&d_prof, 64 * sizeof(long long));
-    (void)hipMemset(d_prof, 0, 64 * sizeof(long long));
-    a.prof = d_prof;
-#endif
     if (a.atomic_out) {
         const maxk_status st = launch_fill_zero(dXs, N * (int64_t)k, s);
         if (st != MAXK_OK) return st;
@@ -774,24 +746,8 @@ maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, 
     (index_bytes == 1 ? launch_tiled_t<TR, DIMC, RC, PPL, uint8_t>(a, lds_bytes, s)                               \
      : index_bytes == 2 ? launch_tiled_t<TR, DIMC, RC, PPL, uint16_t>(a, lds_bytes, s)                            \
                         : launch_tiled_t<TR, DIMC, RC, PPL, int32_t>(a, lds_bytes, s))
-    maxk_status st;
-    if (tiled_positions_per_lane(k) == 8) {
-        if (dim == 256) st = T.TR == 48 ? MAXK_TILED_I(48, 256, 1, 8) : T.TR == 32 ? MAXK_TILED_I(32, 256, 1, 8) : MAXK_TILED_I(16, 256, 1, 8);
-        else st = dim < 256 ? MAXK_TILED_I(16, 0, 1, 8) : MAXK_TILED_I(16, 0, 2, 8);
-    } else {
-        if (dim == 256) st = T.TR == 48 ? MAXK_TILED_I(48, 256, 1, 4) : T.TR == 32 ? MAXK_TILED_I(32, 256, 1, 4) : MAXK_TILED_I(16, 256, 1, 4);
-        else st = dim < 256 ? MAXK_TILED_I(16, 0, 1, 4) : MAXK_TILED_I(16, 0, 2, 4);
-    }
+    const maxk_status st = dim == 256 ? MAXK_TILED_I(16, 256, 1, 4) : dim < 256 ? MAXK_TILED_I(16, 0, 1, 4) : MAXK_TILED_I(16, 0, 2, 4);
 #undef MAXK_TILED_I
-#ifdef MAXK_TILED_PROFILE
-    if (getenv("MAXK_TILED_PROFILE_PRINT")) {
-        long long h[32];
-        (void)hipDeviceSynchronize();
-        (void)hipMemcpy(h, a.prof, sizeof(h), hipMemcpyDeviceToHost);
-        fprintf(stderr, "tiled profile (block 8; per wavefront: total clocks, clocks inside barriers):\n");
-        for (int w = 0; w < kAccWaves + kLoadWaves + 1; ++w) fprintf(stderr, "  wave %2d: %lld %lld\n", w, h[2 * w], h[2 * w + 1]);
-    }
-#endif
     return st;
 }
 

@@ -160,7 +160,8 @@ def check_narrow(dg, H_dev, dY, k, index_bytes, ref_cbsr, dim, rows=None):
         dY16 = _bits_to_dev(dY_bits, dtype)
         refb, refbabs = oracle.sspmm_bwd(g.rowptr, g.col, g.val, oracle.widen(dY_bits, vt), ref_cbsr[1], nodes=rows)
         sp_index32 = sp_index
-        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_SLAB_PULL, maxk.BWD_AUTO):
+        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_SLAB_PULL, maxk.BWD_TILED,
+                     maxk.BWD_AUTO):  # (the tiled kernel takes fp32 dY only: these calls run its slab-pull fallback)
             dg.handle.set_bwd_mode(mode)
             dXs = torch.full((N, k), float("nan"), dtype=torch.float32, device="cuda")
             maxk.maxk_sspmm_bwd_narrow(dg.handle, dY16, sp_index32, dXs)
@@ -199,9 +200,10 @@ def full_pass(dg, H, dY, k, index_bytes, sampled, seed=0, n_random=1500, spmm=Tr
     dX_er, rb3 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_EXPAND_REDUCE, rows)
     dX_auto, rb4 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_AUTO, rows)
     dX_slab, rb5 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_SLAB_PULL, rows)
+    dX_tiled, rb6 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_TILED, rows)
     say(f"    backward ok, worst err/bound pull {rb1:.3f} push {rb2:.3f} expand/reduce {rb3:.3f} auto {rb4:.3f} "
-        f"slab {rb5:.3f} ({time.time() - t0:.1f}s)")
-    for dX in (dX_pull, dX_push, dX_er, dX_auto, dX_slab):
+        f"slab {rb5:.3f} tiled {rb6:.3f} ({time.time() - t0:.1f}s)")
+    for dX in (dX_pull, dX_push, dX_er, dX_auto, dX_slab, dX_tiled):
         check_adjoint(Y, dY_dev, sp_data, dX)
     if spmm:
         rs = check_spmm(dg, H, H_dev, rows)

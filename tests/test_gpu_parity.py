@@ -51,7 +51,8 @@ def test_golden_example_on_gpu():
         Y = torch.empty((N, dim), device="cuda")
         maxk.maxk_spgemm_fwd(gr, sp_data, sp_index, dim, Y)
         assert np.array_equal(Y.cpu().numpy(), np.array(g["Y"], dtype=np.float32))  # small integers: exact
-        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_SLAB_PULL, maxk.BWD_AUTO):
+        for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_SLAB_PULL, maxk.BWD_TILED,
+                     maxk.BWD_AUTO):
             gr.set_bwd_mode(mode)
             dXs = torch.empty((N, k), device="cuda")
             maxk.maxk_sspmm_bwd(gr, to_dev(dY), sp_index, dXs)
@@ -172,6 +173,8 @@ def test_misaligned_views_take_the_scalar_paths():
     check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_PUSH_CSR)
     check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_PULL_CSC)
     check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_EXPAND_REDUCE)
+    check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_SLAB_PULL)
+    check_backward(dg, ref, dY, to_dev(dY), sp_index, maxk.BWD_TILED)  # sp_index off by one byte: runs slab pull
     dxbuf = torch.empty(g.N * k + 1, device="cuda")  # misaligned dXs: the reduce phase takes its scalar path
     dg.handle.set_bwd_mode(maxk.BWD_EXPAND_REDUCE)
     maxk.maxk_sspmm_bwd(dg.handle, to_dev(dY), sp_index, dxbuf[1:].view(g.N, k))
@@ -192,7 +195,7 @@ def test_outputs_are_overwritten_and_calls_repeat():
     maxk.maxk_spgemm_fwd(dg.handle, sp_data, sp_index, 64, Y1)
     ref, refabs = oracle.spgemm_fwd(g.rowptr, g.col, g.val, *oracle.topk_cbsr(H, 8), 64)
     assert np.abs(Y1.cpu().numpy() - ref).max() < 1e-4
-    for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_SLAB_PULL):
+    for mode in (maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR, maxk.BWD_EXPAND_REDUCE, maxk.BWD_SLAB_PULL, maxk.BWD_TILED):
         dg.handle.set_bwd_mode(mode)
         a = torch.full((g.N, 8), 55.0, device="cuda")
         b = torch.full((g.N, 8), -7.0, device="cuda")
@@ -291,7 +294,7 @@ def test_step_captured_in_a_hip_graph_replays_correctly():
     g = synth.graph(name)
     dim, k = synth.CONFIGS[name].dim, 8
     dg = DeviceGraph(g)
-    for mode in (maxk.BWD_SLAB_PULL, maxk.BWD_EXPAND_REDUCE, maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR):
+    for mode in (maxk.BWD_TILED, maxk.BWD_SLAB_PULL, maxk.BWD_EXPAND_REDUCE, maxk.BWD_PULL_CSC, maxk.BWD_PUSH_CSR):
         dg.handle.set_bwd_mode(mode)
         dg.handle.reserve(dim, k)
         Hs = torch.empty((g.N, dim), device="cuda")

@@ -43,8 +43,9 @@ def test_dense_graph_builds():
     info = dg.handle.info()
     assert info["nnz"] == synth.CONFIGS["dense"].nnz == 114_848_855
     assert 15_000 <= info["max_degree"] <= 25_000
-    # dense neighbourhoods: the library's own choice is the L2-tiled pull for every k of the sweep
-    assert all(dg.handle.bwd_choice(256, k) == "slab_pull" for k in synth.CONFIGS["dense"].ks)
+    # dense neighbourhoods: the library's own choice is the LDS-tiled kernel at small k and the L2-tiled pull above
+    want = {8: "tiled", 16: "tiled", 32: "slab_pull", 64: "slab_pull", 96: "slab_pull", 128: "slab_pull"}
+    assert {k: dg.handle.bwd_choice(256, k) for k in synth.CONFIGS["dense"].ks} == want
 
 
 @pytest.mark.parametrize("k", synth.CONFIGS["dense"].ks)
