@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_status_strings_and_version(lib):
     assert lib.maxk_version() >= 100
     assert lib.maxk_status_string(0) == b"ok"
-    for code in (-1, -2, -3, -4):
+    for code in (-1, -2, -3, -4, -5):
         assert lib.maxk_status_string(code) not in (b"ok", b"unknown status")
     assert lib.maxk_status_string(-99) == b"unknown status"
 
@@ -70,6 +70,7 @@ def test_invalid_arguments_are_rejected_without_touching_the_device(lib):
     assert not h
     assert lib.maxk_graph_destroy(None) == 0
     assert lib.maxk_spgemm_fwd(None, fake, fake, 1, 64, 8, fake, None) == INVALID
+    assert lib.maxk_spgemm_fwd_noalloc(None, fake, fake, 1, 64, 8, fake, None) == INVALID  # null handle
     assert lib.maxk_sspmm_bwd(None, fake, fake, 1, 64, 8, fake, None) == INVALID
     assert lib.spmm_baseline(None, fake, 64, fake, None) == INVALID
     assert lib.maxk_graph_reserve(None, 64, 8) == INVALID
