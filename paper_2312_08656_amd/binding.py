@@ -19,7 +19,7 @@ EXPORTS = (
     "maxk_graph_info",
     "maxk_topk_cbsr", "maxk_spgemm_fwd", "maxk_spgemm_fwd_noalloc", "maxk_topk_cbsr_narrow", "maxk_spgemm_fwd_narrow", "maxk_sspmm_bwd",
     "maxk_sspmm_bwd_narrow", "maxk_cbsr_scatter", "spmm_baseline", "maxk_status_string",
-    "maxk_last_hip_error", "maxk_version", "maxk_fwd_private_copies",
+    "maxk_last_hip_error", "maxk_version", "maxk_fwd_private_copies", "maxk_graph_cached_tables",
 )
 
 
@@ -68,6 +68,8 @@ def load_library() -> ctypes.CDLL:
     lib.maxk_status_string.argtypes = [i32]
     lib.maxk_status_string.restype = ctypes.c_char_p
     lib.maxk_fwd_private_copies.argtypes = [i32]
+    lib.maxk_graph_cached_tables.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.maxk_graph_cached_tables.restype = i32
     lib.maxk_fwd_private_copies.restype = i32
     lib.maxk_last_hip_error.argtypes = []
     lib.maxk_version.argtypes = []
@@ -142,6 +144,13 @@ class MaxKGraph:
         _check(load_library().maxk_graph_info(self.handle, *[ctypes.byref(v) for v in vals]), "maxk_graph_info")
         names = ("N", "nnz", "n_fwd_items", "n_split_rows", "max_degree", "workspace_bytes")
         return {n: int(v.value) for n, v in zip(names, vals)}
+
+    def cached_tables(self) -> tuple:
+        """(slab tables, tiled visit lists) the handle holds -- a test hook."""
+        a, b = ctypes.c_int32(), ctypes.c_int32()
+        _check(load_library().maxk_graph_cached_tables(self.handle, ctypes.byref(a), ctypes.byref(b)),
+               "maxk_graph_cached_tables")
+        return int(a.value), int(b.value)
 
     def destroy(self) -> None:
         if self._h:

@@ -879,6 +879,14 @@ MAXK_API const char* maxk_status_string(maxk_status s)
 
 MAXK_API int32_t maxk_fwd_private_copies(int32_t k) { return k < 1 ? MAXK_INVALID_ARGUMENT : fwd_private_copies(k); }
 
+MAXK_API maxk_status maxk_graph_cached_tables(const maxk_graph* g, int32_t* n_slab_tables, int32_t* n_tiled_tables)
+{
+    if (!g) return MAXK_INVALID_ARGUMENT;
+    if (n_slab_tables) *n_slab_tables = (int32_t)g->slab_cache.size();
+    if (n_tiled_tables) *n_tiled_tables = (int32_t)g->tiled_cache.size();
+    return MAXK_OK;
+}
+
 int32_t maxk_last_hip_error(void) { return g_last_hip_error; }
 
 MAXK_API int32_t maxk_version(void) { return 100; }

@@ -136,10 +136,11 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* _
                                                                const IdxT* __restrict__ sp_index,
                                                                const char* __restrict__ packed, int rec_bytes,
                                                                int idx_off,
-                                                               int dim, int k_rt, int nb_rt, float* __restrict__ Y,
-                                                               float* __restrict__ partials)
+                                                               int dim, int k_rt, int nb_rt, int vec_out,
+                                                               float* __restrict__ Y, float* __restrict__ partials)
 {
-    extern __shared__ float lds[];
+    // vec_out: dim % 4 == 0 and Y / partials 16-byte aligned, so that a row is written with 16-byte stores
+    extern __shared__ __attribute__((aligned(16))) float lds[];
     const int k = K ? K : k_rt;
     const int nb = K ? private_copies(K) : nb_rt;
     const int lane = threadIdx.x;
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* _
     __syncthreads();
 
     float* __restrict__ out = (it.slot < 0) ? Y + (int64_t)it.row * dim : partials + (int64_t)it.slot * dim;
-    if ((dim & 3) == 0) {
+    if (vec_out) {
         for (int c = lane * 4; c < dim; c += kWave * 4) {
             float4 acc = *reinterpret_cast<const float4*>(row_buf + c);
             for (int b = 1; b < nb; ++b) {
@@ -233,9 +234,10 @@ maxk_status launch_rmw(const ItemList& L, const int32_t* col, const float* val, 
     dim3 grid((unsigned)L.n_items), block(kWave);
     const int nb = private_copies(k);
     const size_t lds = sizeof(float) * (size_t)((nb * dim + 1) & ~1) + sizeof(int2) * kWave;
+    const int vec_out = dim % 4 == 0 && aligned(Y, 16) && aligned(partials, 16);
 #define MAXK_FWD_RMW(K, R)                                                                                        \
     hipLaunchKernelGGL((spgemm_fwd_rmw_kernel<K, R, PACKED, VT, IdxT>), grid, block, lds, s, L.d_items, col, val, \
-                       sp_data, sp_index, packed, rec_bytes, idx_off, dim, k, nb, Y, partials)
+                       sp_data, sp_index, packed, rec_bytes, idx_off, dim, k, nb, vec_out, Y, partials)
     switch (k) {
         case 8: MAXK_FWD_RMW(8, 8); break;
         case 16: MAXK_FWD_RMW(16, 8); break;

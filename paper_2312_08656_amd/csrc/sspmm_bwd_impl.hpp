@@ -652,13 +652,16 @@ __global__ __launch_bounds__(kWave) void bwd_slab_rowacc_kernel(const int32_t* _
             cur = nxt;
             pos += cnt;
         }
-        // the visit's share of (A^T dY)[j, :] -> LDS, then dXs[j, t] += row[sp_index[j, t]]
+        // the visit's share of (A^T dY)[j, :] -> LDS, then dXs[j, t] += row[sp_index[j, t]].  Lanes read what other
+        // lanes wrote: a barrier after the writes, and one before the next visit overwrites the row (the workgroup
+        // is one wavefront, so these cost a wait for the LDS queue and no more).
 #pragma unroll
         for (int c = 0; c < RC; ++c)
 #pragma unroll
             for (int i = 0; i < EPL; i += 4)
                 *reinterpret_cast<float4*>(row_acc + c * CHUNK + lane * EPL + i) =
                     make_float4(acc[c][i], acc[c][i + 1], acc[c][i + 2], acc[c][i + 3]);
+        __syncthreads();
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int t = lane + h * kWave;
@@ -668,6 +671,7 @@ __global__ __launch_bounds__(kWave) void bwd_slab_rowacc_kernel(const int32_t* _
             const int col = (int)sp_index[j * k + t];
             dXs[j * k + t] += row_acc[col];
         }
+        __syncthreads();
     }
 }
 

@@ -182,6 +182,25 @@ def test_misaligned_views_take_the_scalar_paths():
     assert (np.abs(dxbuf[1:].view(g.N, k).cpu().numpy() - dref) <= 1e-5 * dabs + 1e-6).all()
     dg.handle.set_bwd_mode(maxk.BWD_AUTO)
     check_spmm(dg, H, Hd)
+    # Y itself 4 bytes off a 16-byte boundary: forward (two-array, repacked, 16-bit values) and dense SpMM write
+    # their rows with 4-byte stores then, whatever the hidden width
+    fref, fabs_ = oracle.spgemm_fwd(g.rowptr, g.col, g.val, ref[0], ref[1], dim)
+    sref, sabs = oracle.spmm(g.rowptr, g.col, g.val, H)
+    ybuf = torch.full((g.N * dim + 1,), float("nan"), device="cuda")
+    Yoff = ybuf[1:].view(g.N, dim)
+    assert Yoff.data_ptr() % 16 == 4
+    al_d, al_i = gpu_topk(to_dev(H), k, 1)
+    for sd, si in ((sp_data, sp_index), (al_d, al_i)):
+        Yoff.fill_(float("nan"))
+        maxk.maxk_spgemm_fwd(dg.handle, sd, si, dim, Yoff)
+        assert (np.abs(Yoff.cpu().numpy() - fref) <= 1e-5 * fabs_ + 1e-6).all(), "forward into a misaligned Y"
+    Yoff.fill_(float("nan"))
+    maxk.maxk_spgemm_fwd_noalloc(dg.handle, al_d, al_i, dim, Yoff)
+    assert (np.abs(Yoff.cpu().numpy() - fref) <= 1e-5 * fabs_ + 1e-6).all(), "no-alloc forward into a misaligned Y"
+    Yoff.fill_(float("nan"))
+    maxk.spmm_baseline(dg.handle, to_dev(H), Yoff)
+    assert (np.abs(Yoff.cpu().numpy() - sref) <= 1e-5 * sabs + 1e-6).all(), "dense SpMM into a misaligned Y"
+    assert bool(torch.isnan(ybuf[0]))  # the element before the view was not touched
     dg.close()
 
 
@@ -202,6 +221,49 @@ def test_outputs_are_overwritten_and_calls_repeat():
         maxk.maxk_sspmm_bwd(dg.handle, dYd, sp_index, a)
         maxk.maxk_sspmm_bwd(dg.handle, dYd, sp_index, b)
         assert (a - b).abs().max().item() < 1e-5
+    dg.close()
+
+
+def test_tables_are_built_once_per_shape_and_reserve_builds_them_ahead():
+    """Alternating hidden widths, k and dY formats on one handle never rebuilds a regrouping of A^T; after
+    maxk_graph_reserve* the compute call for that shape adds none either."""
+    g = synth.make_graph(500, 30000, 0, directed=True, self_loops=True, seed=77, weights="normal")
+    dg = DeviceGraph(g)
+    h = dg.handle
+
+    def bwd(dim, k, mode, dtype=torch.float32):
+        h.set_bwd_mode(mode)
+        dY = to_dev(synth.normal_matrix(g.N, dim, dim + k)).to(dtype)
+        H = synth.normal_matrix(g.N, dim, 3)
+        _, si = gpu_topk(to_dev(H), k, 2)
+        out = torch.empty((g.N, k), device="cuda")
+        maxk.maxk_sspmm_bwd_narrow(h, dY, si, out)
+        torch.cuda.synchronize()
+        ref, refabs = oracle.sspmm_bwd(g.rowptr, g.col, g.val, dY.float().cpu().numpy(), oracle.topk_cbsr(H, k)[1])
+        assert (np.abs(out.cpu().numpy() - ref) <= 1e-5 * refabs + 1e-6).all()
+
+    assert h.cached_tables() == (0, 0)
+    h.set_bwd_mode(maxk.BWD_SLAB_PULL)
+    h.reserve(256, 32)
+    h.reserve(384, 32)
+    h.reserve(256, 32, torch.bfloat16)  # 16-bit rows: a slab height of their own
+    n_slab = h.cached_tables()[0]
+    assert 2 <= n_slab <= 3 and h.cached_tables()[1] == 0  # (two widths may share a slab height)
+    h.set_bwd_mode(maxk.BWD_TILED)
+    h.reserve(256, 8)
+    h.reserve(256, 32)
+    assert h.cached_tables() == (n_slab, 2)
+    for _ in range(3):  # alternate shapes, formats and kernels: nothing new is built
+        bwd(256, 32, maxk.BWD_SLAB_PULL)
+        bwd(384, 32, maxk.BWD_SLAB_PULL)
+        bwd(256, 32, maxk.BWD_SLAB_PULL, torch.bfloat16)
+        bwd(256, 8, maxk.BWD_TILED)
+        bwd(256, 32, maxk.BWD_TILED)
+        assert h.cached_tables() == (n_slab, 2)
+    bwd(128, 16, maxk.BWD_TILED)  # a shape nobody reserved: built by the call, once
+    bwd(128, 16, maxk.BWD_TILED)
+    assert h.cached_tables()[1] == 3
+    h.set_bwd_mode(maxk.BWD_AUTO)
     dg.close()
 
 
