@@ -7,7 +7,7 @@ HIP library, so neither side ever sees values produced by the other.
 
 The heavy lifting (R-MAT descent, dedup, CSR build, Box-Muller) is plain C with
 OpenMP in ``synth.c``; this module compiles it on first use with gcc, loads it
-with ctypes and names the five benchmark configurations.
+with ctypes and names the benchmark configurations.
 """
 from __future__ import annotations
 
@@ -107,6 +107,14 @@ CONFIGS: Dict[str, Config] = {
                stands_for="ogbn-products row of Table 1"),
         Config("wide_hidden", 716_847, 13_954_819, 20, (0.65, 0.15, 0.15), directed=True, dim=384,
                ks=(32, 96, 192), index_bytes=2, tie_percent=5, stands_for="Yelp row of Table 1, hidden 384"),
+        # three more degree profiles from the average-degree > 50 group of the kernel evaluation (Sec. 5.2):
+        # a tiny, very dense graph; one denser than the headline; a large one of moderate degree
+        Config("ddi_like", 4_267, 1_067_911, 13, (0.30, 0.25, 0.25), dim=256, ks=(8, 16, 32, 64),
+               stands_for="ddi row of Table 1"),
+        Config("proteins_like", 132_534, 39_561_252, 18, (0.40, 0.22, 0.22), dim=256, ks=(8, 16, 32, 64),
+               stands_for="ogbn-proteins row of Table 1"),
+        Config("ppa_like", 576_289, 21_231_931, 20, (0.45, 0.22, 0.22), dim=256, ks=(8, 16, 32, 64),
+               stands_for="ppa row of Table 1"),
     ]
 }
 

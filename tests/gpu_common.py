@@ -74,6 +74,31 @@ def sample_rows(g, n_random, seed, include_longest=8):
     return np.unique(np.concatenate(picks)).astype(np.int64)
 
 
+def slab_range_edge_nodes(g, dim, slab_kb=3584, val_bytes=4):
+    """Destinations at the seams of the slab-pull kernels' work split.  A launch covers one slab of source rows; its
+    (slab, destination) visits, in destination order, are dealt to wavefronts in groups and the groups are cut into
+    eight contiguous ranges, one per XCD.  Returns, for the first, a middle and the last slab and for every group size
+    the kernels use, the first and the last destination of each range (the group size depends on k and on which of
+    the two kernel forms runs, so all of them are taken)."""
+    slab_rows = max(slab_kb * 1024 // (dim * val_bytes), 64)
+    n_slabs = (g.N + slab_rows - 1) // slab_rows
+    picks = []
+    for sl in sorted({0, n_slabs // 2, n_slabs - 1}):
+        lo, hi = sl * slab_rows, min(g.N, (sl + 1) * slab_rows)
+        dests = np.unique(g.col[g.rowptr[lo]:g.rowptr[hi]])  # the slab's visits, in the order the kernel lists them
+        nv = dests.shape[0]
+        if nv == 0:
+            continue
+        for group in (1, 2, 4, 8, 16, 32, 64):
+            tasks = (nv + group - 1) // group
+            per_xcd = (tasks + 7) // 8
+            for x in range(8):
+                first, last = x * per_xcd * group, min(nv, (x + 1) * per_xcd * group) - 1
+                if first < nv:
+                    picks += [dests[first], dests[max(first, last)]]
+    return np.unique(np.asarray(picks, dtype=np.int64))
+
+
 def check_forward(dg, ref_cbsr, sp_data_dev, sp_index_dev, dim, rows=None):
     g = dg.host
     Y = torch.full((g.N, dim), float("nan"), dtype=torch.float32, device="cuda")
@@ -193,6 +218,8 @@ def full_pass(dg, H, dY, k, index_bytes, sampled, seed=0, n_random=1500, spmm=Tr
     ref = check_topk(H, k, sp_data, sp_index)
     say(f"    top-k ok ({time.time() - t0:.1f}s)")
     rows = sample_rows(g, n_random, seed) if sampled else None
+    if sampled:
+        rows = np.unique(np.concatenate([rows, slab_range_edge_nodes(g, dim)]))
     Y, rf = check_forward(dg, ref, sp_data, sp_index, dim, rows)
     say(f"    forward ok, worst err/bound {rf:.3f} ({time.time() - t0:.1f}s)")
     dX_pull, rb1 = check_backward(dg, ref, dY, dY_dev, sp_index, maxk.BWD_PULL_CSC, rows)
