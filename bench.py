@@ -29,14 +29,33 @@ if str(ROOT) not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# L2 <-> fabric bytes per API call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what a plain
-# 1 GiB copy reads on the same counters: x2.0 and x1.0), from profiles/dense_k32_step_trace_and_counters.txt.
-# Keyed by (workload, k, entry point, backward mode); anything else reports null.
-MEASURED_TRAFFIC_BYTES = {
-    ("dense", 32, "maxk_spgemm_fwd", None): 21.06e9,
-    ("dense", 32, "maxk_sspmm_bwd", "auto"): 10.95e9,
-    ("dense", 32, "maxk_sspmm_bwd", "slab"): 10.95e9,
-}
+L2_TO_L1_BYTES_PER_CLK_PER_CU, N_CU, CLOCK_HZ = 64.0, 256, 2.4e9  # vector L1 fill path; MI355X CUs and peak clock
+INFINITY_CACHE_BYTES = 256e6
+
+
+def measured_traffic(workload: str, k: int, entry: str, kernel: str):
+    """L2 <-> fabric bytes per API call from the committed rocprofv3 counter summaries under profiles/ (lines of the
+    form `traffic_bytes_per_call workload=... k=... entry=... kernel=... bytes=...`, written from FETCH_SIZE and
+    WRITE_SIZE runs scaled by a plain copy of known size); None when no summary covers this case."""
+    want = {"workload": workload, "k": str(k), "entry": entry, "kernel": kernel}
+    for f in sorted((ROOT / "profiles").glob("*.txt")):
+        try:
+            lines = f.read_text().splitlines()
+        except OSError:
+            continue
+        for line in lines:
+            if not line.startswith("traffic_bytes_per_call"):
+                continue
+            kv = dict(tok.split("=", 1) for tok in line.split()[1:] if "=" in tok)
+            if all(kv.get(a) == b for a, b in want.items()) and "bytes" in kv:
+                return {"bytes": float(kv["bytes"]), "source": f"profiles/{f.name}"}
+    return None
+
+
+def lines_touched(dim: int, k: int) -> float:
+    """Expected 128-byte lines of a fp32 dY row that k distinct random columns fall into."""
+    per_row = dim / 32.0
+    return per_row if per_row <= 1 else per_row * (1.0 - (1.0 - 1.0 / per_row) ** k)
 
 
 def algorithmic_bytes(N: int, nnz: int, dim: int, k: int, index_bytes: int = 1, value_bytes: int = 4) -> dict:
@@ -79,7 +98,7 @@ def main() -> int:
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-k table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--sweep-reps", type=int, default=20)
-    ap.add_argument("--bwd-mode", default="auto", choices=["auto", "pull", "push", "expand", "slab"],
+    ap.add_argument("--bwd-mode", default="auto", choices=["auto", "pull", "push", "expand", "slab", "tiled"],
                     help="backward kernel used in the timed steps (default: the library's choice)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference point for rocprofv3 byte counters)")
@@ -117,9 +136,11 @@ def main() -> int:
     t_res = time.time()
     kmax = max(max(cfg.ks), k0)
     bwd_modes = {"auto": maxk.BWD_AUTO, "pull": maxk.BWD_PULL_CSC, "push": maxk.BWD_PUSH_CSR,
-                 "expand": maxk.BWD_EXPAND_REDUCE, "slab": maxk.BWD_SLAB_PULL}
+                 "expand": maxk.BWD_EXPAND_REDUCE, "slab": maxk.BWD_SLAB_PULL, "tiled": maxk.BWD_TILED}
     gr.set_bwd_mode(bwd_modes[args.bwd_mode])
     gr.reserve(dim, kmax)
+    for kk in sorted(set(cfg.ks) | {k0}):
+        gr.reserve(dim, kk)  # builds whatever the backward kernel chosen for this k needs
     torch.cuda.synchronize()
     t_res = time.time() - t_res
     Y = torch.empty((N, dim), device="cuda")
@@ -167,9 +188,11 @@ def main() -> int:
     dom_name, dom_ms, dom_bytes = max((("maxk_spgemm_fwd", t_fwd, ab["fwd"]), ("maxk_sspmm_bwd", t_bwd, ab["bwd"])),
                                       key=lambda t: t[1])
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, k0, dom_name, args.bwd_mode if "bwd" in dom_name else None))
-    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+    dom_kernel = gr.bwd_choice(dim, k0) if "bwd" in dom_name else "rmw"
+    tr = measured_traffic(cfg.name, k0, dom_name, dom_kernel)
+    roofline = {"bound": "hbm", "kernel": dom_name, "device_kernel": dom_kernel, "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None if tr is None else tr["bytes"], "traffic_source": None if tr is None else tr["source"],
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": round(dom_ms, 4)}
 
     if args.calibrate_copy:
@@ -217,7 +240,8 @@ def main() -> int:
                             f"fwd_{name}_values_hbm_frac": round(b16["fwd"] / (t16 * 1e-3) / 8e12, 4)})
                 del sd16
             for mode, tag in ((maxk.BWD_PUSH_CSR, "bwd_push"), (maxk.BWD_PULL_CSC, "bwd_pull"),
-                              (maxk.BWD_EXPAND_REDUCE, "bwd_expand_reduce"), (maxk.BWD_SLAB_PULL, "bwd_slab_pull")):
+                              (maxk.BWD_EXPAND_REDUCE, "bwd_expand_reduce"), (maxk.BWD_SLAB_PULL, "bwd_slab_pull"),
+                              (maxk.BWD_TILED, "bwd_tiled")):
                 gr.set_bwd_mode(mode)
                 reps = max(3, args.sweep_reps // 4)
                 tb, tb_med = timeit(lambda: maxk.maxk_sspmm_bwd(gr, dYd, si, dx), reps, warm=1)
@@ -235,8 +259,18 @@ def main() -> int:
                         "bwd_ms": round(tb, 4), "bwd_edges_k_per_s": nnz * k / (tb * 1e-3),
                         "bwd_hbm_frac": round(b["bwd"] / (tb * 1e-3) / 8e12, 4),
                         "bwd_speedup_vs_spmm": round(spmm_ms / tb, 2),
-                        "fwd_bwd_edges_k_per_s": 2.0 * nnz * k / ((tf + tb) * 1e-3),
-                        "fwd_bwd_hbm_frac": round((b["fwd"] + b["bwd"]) / ((tf + tb) * 1e-3) / 8e12, 4)})
+                        "fwd_bwd_edges_k_per_s": 2.0 * nnz * k / ((tf + tb) * 1e-3)})
+            # What binds the backward kernels below the HBM roofline: the slab-pull forms fetch whole 128-byte lines
+            # of dY rows from L2 into the vector L1 (the lines that k columns touch; all of a row once k >= dim/8),
+            # and that path moves 64 bytes per clock per CU.  The time that ceiling allows, and the share reached:
+            ln = dim / 32.0 if 8 * k >= dim else lines_touched(dim, k)
+            ceil_ms = nnz * ln * 128.0 / (L2_TO_L1_BYTES_PER_CLK_PER_CU * N_CU * CLOCK_HZ) * 1e3
+            row.update({"bwd_slab_pull_lines_per_entry": round(ln, 2), "bwd_slab_pull_l1_fill_ceiling_ms": round(ceil_ms, 3),
+                        "bwd_slab_pull_share_of_l1_fill_ceiling": round(ceil_ms / row["bwd_slab_pull_ms"], 3)})
+            # a fraction above 1 means the gathered table sits in the Infinity Cache, not that HBM ran past its peak
+            cbsr_bytes, dy_bytes = N * k * (4 + ib), 4 * N * dim
+            row["note"] = ("CBSR %.0f MB and dY %.0f MB; gathers of a table that fits the %.0f MB Infinity Cache are not "
+                           "bound by HBM" % (cbsr_bytes / 1e6, dy_bytes / 1e6, INFINITY_CACHE_BYTES / 1e6))
             per_k.append(row)
             del sd, si, dx
 
@@ -282,8 +316,8 @@ def main() -> int:
                               "sspmm_bwd": round(t_bwd, 4)},
         "hbm_frac_by_algorithmic_bytes": {"fwd": round(ab["fwd"] / (t_fwd * 1e-3) / 8e12, 4),
                                           "bwd": round(ab["bwd"] / (t_bwd * 1e-3) / 8e12, 4),
-                                          "topk": round(ab["topk"] / (t_topk * 1e-3) / 8e12, 4),
-                                          "fwd+bwd": round((ab["fwd"] + ab["bwd"]) / ((t_fwd + t_bwd) * 1e-3) / 8e12, 4)},
+                                          "topk": round(ab["topk"] / (t_topk * 1e-3) / 8e12, 4)},
+        "target": "forward and backward EACH at >= 0.5 of the HBM roofline by algorithmic bytes, per k (see per_k)",
         "spmm_baseline_ms": None if spmm_ms is None else round(spmm_ms, 4),
         "per_k": per_k,
         "roofline": roofline,
