@@ -128,6 +128,7 @@ def test_proteins_like_every_element(k):
     dg, H, dY = _setup("proteins_like")
     assert dg.handle.info()["nnz"] == synth.CONFIGS["proteins_like"].nnz == 79_255_038
     say(f"  proteins_like k={k}: library's backward choice {dg.handle.bwd_choice(256, k)}")
+    assert dg.handle.bwd_choice(256, k) == {8: "tiled", 32: "slab_pull"}[k]  # the faster kernel by measurement
     full_pass(dg, H, dY, k, 1, sampled=False, spmm=(k == 32), narrow=False)
 
 
