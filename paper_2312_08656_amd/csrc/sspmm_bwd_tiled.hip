@@ -10,22 +10,23 @@
 // are LDS traffic.  All workgroups of an XCD sweep the same source range at the same time, so the rows come from that
 // XCD's L2.
 //
-// Work assignment inside a workgroup (9 wavefronts):
-//   - wavefronts 4..7 only load: each keeps a register queue of the next tiles' rows (plain 16-byte loads, several
-//     tiles ahead: the queue depth is what hides the L2 latency) and writes one tile per step into one of two LDS row
-//     buffers;
-//   - wavefronts 0..3 only accumulate.  A "visit" is one (tile, destination) pair with at least one entry; k/4 lanes
+// Work assignment inside a workgroup (13 wavefronts):
+//   - wavefronts 8..11 only load: each keeps a register queue of the next four tiles' rows (plain 16-byte loads; the
+//     queue depth is what hides the L2 latency) and writes one tile per step into one of two LDS row buffers;
+//   - wavefronts 0..7 only accumulate.  A "visit" is one (tile, destination) pair with at least one entry; k/4 lanes
 //     work on it, four CBSR positions each, so a wave instruction covers a "set" of 64/(k/4) visits.  The visits of a
 //     tile have distinct destinations, so the sets of one tile can be worked on by different wavefronts at the same
-//     time without two lanes ever touching one accumulator; set s of the workgroup's list goes to wavefront s % 4.
+//     time without two lanes ever touching one accumulator; set s of the workgroup's list goes to wavefront s % 8,
+//     counted through the whole list, so each wavefront walks an arithmetic progression of sets and fetches its
+//     records eight sets ahead; a directory (one scalar load per tile) tells where a tile's sets end.
 //     A visit's first entry sits in the visit record, a second one in a parallel array, further ones (rare) in a chain;
-//   - wavefront 8 touches cache lines of the tiles further ahead so that they are in L2 when the loaders ask.
+//   - wavefront 12 touches cache lines of the tiles further ahead so that they are in L2 when the loaders ask.
 //   One workgroup barrier per tile hands a row buffer from the loaders to the accumulators and orders the
 //   accumulator updates of consecutive tiles.
 //
 // The visit lists are built once per (D, k/4) by sorting the entries of A^T by (destination set, tile, destination,
-// source); every tile's list is padded to a multiple of four sets, so that each accumulating wavefront walks an
-// arithmetic progression of sets and can fetch its records far ahead without looking at the directory.
+// source); every tile's list is padded to whole sets.  When there are more CUs than destination sets, the source rows
+// are cut into ranges, one workgroup per (range, set), and the partial sums are added to dXs with fp32 atomics.
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
 
 #include <algorithm>
