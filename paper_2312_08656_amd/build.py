@@ -24,12 +24,13 @@ HIPCC_FLAGS = [
 def build(verbose: bool = False) -> Path:
     """Compile every translation unit and link the shared library (always rebuilds)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    extra = os.environ.get("MAXK_HIPCC_EXTRA", "").split()  # e.g. -DMAXK_FWD_COPY_PAD=4 for an experiment build
     objdir = HERE / "_build"
     objdir.mkdir(exist_ok=True)
 
     def compile_one(src: str) -> Path:
         obj = objdir / (src + ".o")
-        cmd = [hipcc, *HIPCC_FLAGS, "-c", str(CSRC / src), "-o", str(obj)]
+        cmd = [hipcc, *HIPCC_FLAGS, *extra, "-c", str(CSRC / src), "-o", str(obj)]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

@@ -41,6 +41,14 @@ __host__ __device__ constexpr int private_copies(int k)
 
 constexpr size_t kMaxPrivateLds = 40 * 1024;  // above this the private copies cost too much occupancy
 
+// Floats between the end of one private copy and the start of the next (a multiple of 4).  Padding shifts the copies
+// against each other in the LDS banks; measured without effect (the columns of different entries are unrelated, so
+// their bank conflicts are those of random addresses), hence 0.
+#ifndef MAXK_FWD_COPY_PAD
+#define MAXK_FWD_COPY_PAD 0
+#endif
+constexpr int kCopyPad = MAXK_FWD_COPY_PAD;
+
 // implemented once per storage format (spgemm_fwd_f32.hip, _bf16.hip, _f16.hip)
 template <int VT>
 maxk_status launch_fwd_format(const ItemList& L, const int32_t* col, const float* val, const void* sp_data,
@@ -145,13 +153,14 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* _
     const int nb = K ? private_copies(K) : nb_rt;
     const int lane = threadIdx.x;
     float* __restrict__ row_buf = lds;                                         // nb copies of the output row
-    int2* __restrict__ entry_buf = reinterpret_cast<int2*>(lds + ((nb * dim + 1) & ~1));  // 64 staged (col, val)
+    const int cs = dim + kCopyPad;                                             // floats from one copy to the next
+    int2* __restrict__ entry_buf = reinterpret_cast<int2*>(lds + ((nb * cs + 1) & ~1));  // 64 staged (col, val)
     const WorkItem it = items[blockIdx.x];
-    if (((nb * dim) & 3) == 0) {
-        for (int c = lane * 4; c < nb * dim; c += kWave * 4)
+    if (((nb * cs) & 3) == 0) {
+        for (int c = lane * 4; c < nb * cs; c += kWave * 4)
             *reinterpret_cast<float4*>(row_buf + c) = make_float4(0.f, 0.f, 0.f, 0.f);
     } else {
-        for (int c = lane; c < nb * dim; c += kWave) row_buf[c] = 0.f;
+        for (int c = lane; c < nb * cs; c += kWave) row_buf[c] = 0.f;
     }
 
     for (int base = it.begin; base < it.end; base += kWave) {
@@ -176,11 +185,11 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* _
                 if constexpr (PACKED) {
                     const char* rec = packed + (int64_t)ed.x * rec_bytes;
                     d[r] = widen_value<VT>(reinterpret_cast<const value_store_t<VT>*>(rec)[t]);
-                    at[r] = (e % nb) * dim + (int)reinterpret_cast<const IdxT*>(rec + idx_off)[t];
+                    at[r] = (e % nb) * cs + (int)reinterpret_cast<const IdxT*>(rec + idx_off)[t];
                 } else {
                     const int64_t off = (int64_t)ed.x * k + t;
                     d[r] = widen_value<VT>(sp_data[off]);
-                    at[r] = (e % nb) * dim + (int)sp_index[off];
+                    at[r] = (e % nb) * cs + (int)sp_index[off];
                 }
             }
 #pragma unroll
@@ -199,7 +208,7 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* _
         for (int c = lane * 4; c < dim; c += kWave * 4) {
             float4 acc = *reinterpret_cast<const float4*>(row_buf + c);
             for (int b = 1; b < nb; ++b) {
-                const float4 x = *reinterpret_cast<const float4*>(row_buf + b * dim + c);
+                const float4 x = *reinterpret_cast<const float4*>(row_buf + b * cs + c);
                 acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
             }
             *reinterpret_cast<float4*>(out + c) = acc;
@@ -207,7 +216,7 @@ __global__ __launch_bounds__(kWave) void spgemm_fwd_rmw_kernel(const WorkItem* _
     } else {
         for (int c = lane; c < dim; c += kWave) {
             float acc = row_buf[c];
-            for (int b = 1; b < nb; ++b) acc += row_buf[b * dim + c];
+            for (int b = 1; b < nb; ++b) acc += row_buf[b * cs + c];
             out[c] = acc;
         }
     }
@@ -233,7 +242,7 @@ maxk_status launch_rmw(const ItemList& L, const int32_t* col, const float* val, 
     if (L.n_items > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
     dim3 grid((unsigned)L.n_items), block(kWave);
     const int nb = private_copies(k);
-    const size_t lds = sizeof(float) * (size_t)((nb * dim + 1) & ~1) + sizeof(int2) * kWave;
+    const size_t lds = sizeof(float) * (size_t)((nb * (dim + kCopyPad) + 1) & ~1) + sizeof(int2) * kWave;
     const int vec_out = dim % 4 == 0 && aligned(Y, 16) && aligned(partials, 16);
 #define MAXK_FWD_RMW(K, R)                                                                                        \
     hipLaunchKernelGGL((spgemm_fwd_rmw_kernel<K, R, PACKED, VT, IdxT>), grid, block, lds, s, L.d_items, col, val, \
