@@ -3,14 +3,24 @@
 // One 64-lane wavefront owns one row of H, held entirely in registers
 // (E values per lane).  The paper's kernel bisects a floating-point pivot
 // between min and max and stops after at most 10 rounds, which cannot separate
-// equal values at rank k.  Here the k-th largest value is found EXACTLY by a
-// most-significant-bit-first radix descent on order-preserving integer keys:
-// each step is E compares + E wave ballots + scalar popcounts, no LDS and no
-// barrier, and the descent stops early as soon as a prefix keeps exactly k
-// entries (the usual case for continuous data, after ~10 bits).  Ties at the
-// k-th value are resolved toward the lower column with ballot prefix counts,
-// and the same prefix counts give every survivor its slot in the CBSR row, so
-// indices come out ascending.
+// equal values at rank k.  Here the selection is EXACT, in two stages.
+// Stage 1 is the paper's idea made exact: bisect a pivot on the value axis
+// between -max|x| and +max|x|, but stop only when the pivot keeps exactly k
+// entries (any such pivot gives the one correct set); a step is E compares + E
+// wave ballots + scalar popcounts, no LDS and no barrier, and for continuous
+// data about 8 steps are enough whatever the exponent range (the step count
+// is log2(range / gap at rank k)).  The kernel is bound by scalar-unit issue
+// (~12 scalar instructions per step, one scalar instruction per clock per CU),
+// so halving the steps is what halves its time.
+// Stage 2 runs only for rows stage 1 cannot settle (ties at rank k, infinities,
+// k = dim): a most-significant-bit-first radix descent on order-preserving
+// integer keys finds the k-th largest value itself, and ties at that value are
+// resolved toward the lower column with ballot prefix counts.  The same prefix
+// counts give every survivor its slot in the CBSR row, so indices come out
+// ascending.
+#include <algorithm>
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace maxk {
@@ -33,6 +43,26 @@ template <int V>
 __device__ __forceinline__ int column_of(int lane, int e)
 {
     return (e / V) * (kWave * V) + lane * V + (e % V);
+}
+
+// Largest value of a non-negative quantity over the wavefront, as a wave-uniform bit pattern.  Data-parallel-primitive
+// moves: a running maximum over the 16 lanes of each row (shifts by 1, 2, 4, 8; lanes shifted in from outside read 0),
+// then lane 15 of each row into the next row and lane 31 into the upper half; lane 63 ends up with the result.
+__device__ __forceinline__ uint32_t wave_max_nonneg(float x)
+{
+    auto step = [](float v, auto ctrl, auto rows) {
+        const int moved = __builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), decltype(ctrl)::value,
+                                                      decltype(rows)::value, 0xF, true);
+        return fmaxf(v, __uint_as_float((uint32_t)moved));
+    };
+    using std::integral_constant;
+    x = step(x, integral_constant<int, 0x111>{}, integral_constant<int, 0xF>{});  // row_shr:1
+    x = step(x, integral_constant<int, 0x112>{}, integral_constant<int, 0xF>{});  // row_shr:2
+    x = step(x, integral_constant<int, 0x114>{}, integral_constant<int, 0xF>{});  // row_shr:4
+    x = step(x, integral_constant<int, 0x118>{}, integral_constant<int, 0xF>{});  // row_shr:8
+    x = step(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});  // row_bcast:15 into rows 1 and 3
+    x = step(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});  // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(x), 63);
 }
 
 // pos[e] = number of flagged elements that precede (lane, e) in column order
@@ -60,96 +90,187 @@ __device__ __forceinline__ void column_order_prefix(const bool (&flag)[E], int (
     }
 }
 
-// VT: storage format of the values written (MAXK_VALUE_*); selection always works on the fp32 input
-template <int E, int V, int VT, typename IdxT>
-__global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict__ H, int64_t N, int dim, int k,
-                                                        value_store_t<VT>* __restrict__ sp_data,
-                                                        IdxT* __restrict__ sp_index)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t row = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (row >= N) return;
-    const float* __restrict__ h = H + row * (int64_t)dim;
+constexpr int kPivotSteps = 16;  // bisection steps before a row is handed to the radix descent (99 % need <= 14)
 
-    float v[E];
-    uint32_t key[E];
+// One row of H into registers: chunks of 64*V columns, V consecutive columns per lane.  Lanes past the row hold
+// copies of its last chunk; select_row replaces them.  Nothing here touches the loaded values, so the loads of the
+// rows ahead stay in flight until the row is used.
+template <int E, int V>
+__device__ __forceinline__ void load_row(const float* __restrict__ h, int dim, int lane, float (&v)[E])
+{
 #pragma unroll
     for (int c = 0; c < E / V; ++c) {
         const int base = c * (kWave * V) + lane * V;
+        // every lane loads (lanes past the row re-read its last chunk and drop the result), so that no branch
+        // surrounds the load and its place among the memory operations in flight is fixed
+        const bool in = base < dim;  // dim % V == 0 on the vector paths
+        const int at = in ? base : dim - V;
         if constexpr (V == 4) {
-            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            const bool in = base < dim;  // dim % 4 == 0 on this path
-            if (in) x = *reinterpret_cast<const float4*>(h + base);
+            const float4 x = *reinterpret_cast<const float4*>(h + at);
             v[c * 4 + 0] = x.x; v[c * 4 + 1] = x.y; v[c * 4 + 2] = x.z; v[c * 4 + 3] = x.w;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) key[c * 4 + j] = in ? order_key(v[c * 4 + j]) : 0u;
         } else if constexpr (V == 2) {
-            float2 x = make_float2(0.f, 0.f);
-            const bool in = base < dim;  // dim % 2 == 0 on this path
-            if (in) x = *reinterpret_cast<const float2*>(h + base);
+            const float2 x = *reinterpret_cast<const float2*>(h + at);
             v[c * 2 + 0] = x.x; v[c * 2 + 1] = x.y;
-#pragma unroll
-            for (int j = 0; j < 2; ++j) key[c * 2 + j] = in ? order_key(v[c * 2 + j]) : 0u;
         } else {
 #pragma unroll
-            for (int j = 0; j < V; ++j) {
-                const bool in = base + j < dim;
-                v[c * V + j] = in ? h[base + j] : 0.f;
-                key[c * V + j] = in ? order_key(v[c * V + j]) : 0u;  // 0 ranks below every non-NaN key
-            }
+            for (int j = 0; j < V; ++j) v[c * V + j] = h[base + j < dim ? base + j : dim - 1];
         }
     }
+}
 
-    // k-th largest key by MSB-first descent; `exact` = the prefix already keeps exactly k.
-    // Everything but the compares is wave-uniform; readfirstlane tells the compiler so, which keeps
-    // the prefix, the candidate and the counts in scalar registers (4 vector compares per step).
-    uint32_t prefix = 0u;
-    bool exact = false;
+// Selection and CBSR packing of one row held in registers.  `stage` is this wavefront's own LDS area of 2*k words:
+// the survivors are put there in CBSR order and leave as whole-row stores.
+// VT: storage format of the values written (MAXK_VALUE_*); selection always works on the fp32 input
+// PAD: the row is shorter than the E*64 columns the lanes cover
+template <int E, int V, bool PAD, int VT, typename IdxT>
+__device__ __forceinline__ void select_row(const float (&raw)[E], int dim, int k, int lane,
+                                           uint32_t* __restrict__ stage, value_store_t<VT>* __restrict__ od,
+                                           IdxT* __restrict__ oi)
+{
+    // columns past `dim` count as -inf: below every real entry in either stage, never selected
+    float v[E];
+    float amax = 0.f;  // largest magnitude of the row (the padding does not count)
 #pragma unroll
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t cand = prefix | (1u << bit);
-        int cnt = 0;
+    for (int e = 0; e < E; ++e) {
+        const bool in = !PAD || column_of<V>(lane, e) < dim;
+        v[e] = in ? raw[e] : -__builtin_inff();
+        amax = fmaxf(amax, in ? fabsf(raw[e]) : 0.f);
+    }
+
+    // Stage 1: bisection of a pivot on the value axis.  count(x >= lo) > k > count(x >= hi) is kept until a pivot
+    // keeps exactly k.  Everything but the compares is wave-uniform; readfirstlane tells the compiler so, which
+    // keeps the bounds, the pivot and the counts in scalar registers (E vector compares per step).
+    const uint32_t amax_bits = wave_max_nonneg(amax);
+    float pivot = 0.f;
+    int kept = -1;  // entries the last pivot keeps
+    if (amax_bits < 0x7F800000u && k < dim) {  // finite row (k = dim: every pivot above -max|x| keeps too few)
+        uint32_t lo = amax_bits | 0x80000000u, hi = amax_bits;
+        for (int step = 0; step < kPivotSteps; ++step) {
+            const float mid = 0.5f * __uint_as_float(lo) + 0.5f * __uint_as_float(hi);
+            const uint32_t mid_bits = (uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(mid));
+            pivot = __uint_as_float(mid_bits);
+            int cnt = 0;
 #pragma unroll
-        for (int e = 0; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= cand));
-        cnt = __builtin_amdgcn_readfirstlane(cnt);
-        if (cnt >= k) {
-            prefix = cand;
-            if (cnt == k) { exact = true; break; }
+            for (int e = 0; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[e] >= pivot));
+            kept = __builtin_amdgcn_readfirstlane(cnt);
+            if (kept == k) break;
+            if (kept > k) lo = mid_bits; else hi = mid_bits;
         }
     }
 
     bool sel[E];
-    if (exact) {
+    if (kept == k) {
 #pragma unroll
-        for (int e = 0; e < E; ++e) sel[e] = key[e] >= prefix;
+        for (int e = 0; e < E; ++e) sel[e] = v[e] >= pivot;
     } else {
-        // prefix is the k-th largest key and more than k entries are >= it: take all
-        // strictly larger ones, then the leftmost (k - those) of the equal ones
-        bool eq[E];
-        int greater = 0;
+        // Stage 2 (rows without such a pivot within kPivotSteps): k-th largest key by MSB-first descent;
+        // `exact` = the prefix already keeps exactly k.  Padding columns get key 0, below every non-NaN key.
+        uint32_t key[E];
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            eq[e] = key[e] == prefix;
-            greater += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] > prefix));
+        for (int e = 0; e < E; ++e) key[e] = (!PAD || column_of<V>(lane, e) < dim) ? order_key(v[e]) : 0u;
+        uint32_t prefix = 0u;
+        bool exact = false;
+#pragma unroll 1
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t cand = prefix | (1u << bit);
+            int cnt = 0;
+#pragma unroll
+            for (int e = 0; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= cand));
+            cnt = __builtin_amdgcn_readfirstlane(cnt);
+            if (cnt >= k) {
+                prefix = cand;
+                if (cnt == k) { exact = true; break; }
+            }
         }
-        const int need = k - greater;
-        int rank[E];
-        column_order_prefix<E, V>(eq, rank);
+        if (exact) {
 #pragma unroll
-        for (int e = 0; e < E; ++e) sel[e] = key[e] > prefix || (eq[e] && rank[e] < need);
+            for (int e = 0; e < E; ++e) sel[e] = key[e] >= prefix;
+        } else {
+            // prefix is the k-th largest key and more than k entries are >= it: take all
+            // strictly larger ones, then the leftmost (k - those) of the equal ones
+            bool eq[E];
+            int greater = 0;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                eq[e] = key[e] == prefix;
+                greater += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] > prefix));
+            }
+            const int need = k - greater;
+            int rank[E];
+            column_order_prefix<E, V>(eq, rank);
+#pragma unroll
+            for (int e = 0; e < E; ++e) sel[e] = key[e] > prefix || (eq[e] && rank[e] < need);
+        }
     }
 
     int pos[E];
     column_order_prefix<E, V>(sel, pos);
-    value_store_t<VT>* __restrict__ od = sp_data + row * (int64_t)k;
-    IdxT* __restrict__ oi = sp_index + row * (int64_t)k;
+    // survivors -> LDS in CBSR order (value bits, then column), then whole-row stores: t-th survivor by lane t.
+    // LDS operations of one wavefront execute in program order, so no barrier is needed inside the wavefront.
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         if (sel[e]) {
-            od[pos[e]] = narrow_value<VT>(v[e]);
-            oi[pos[e]] = (IdxT)column_of<V>(lane, e);
+            stage[pos[e]] = __float_as_uint(v[e]);
+            stage[k + pos[e]] = (uint32_t)column_of<V>(lane, e);
         }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (k <= kWave) {  // one store of each kind: the usual case, and a fixed number of memory operations
+        if (lane < k) {
+            od[lane] = narrow_value<VT>(__uint_as_float(stage[lane]));
+            oi[lane] = (IdxT)stage[k + lane];
+        }
+    } else {
+        for (int t = lane; t < k; t += kWave) {
+            od[t] = narrow_value<VT>(__uint_as_float(stage[t]));
+            oi[t] = (IdxT)stage[k + t];
+        }
+    }
+    __builtin_amdgcn_wave_barrier();  // the next row's survivors go to the same area
+}
+
+// One wavefront owns `rows_per_wave` consecutive rows and keeps the loads of the next two rows in flight while it
+// selects from the current one: a row is only 4*dim bytes, and with one row per wavefront the kernel waited on
+// memory latency (32 wavefronts per CU x 1 KB in flight).
+template <int E, int V, bool PAD, int VT, typename IdxT>
+__global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict__ H, int64_t N, int dim, int k,
+                                                        int rows_per_wave, value_store_t<VT>* __restrict__ sp_data,
+                                                        IdxT* __restrict__ sp_index)
+{
+    extern __shared__ uint32_t topk_stage[];  // 2*k words per wavefront
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform: rows and loop are scalar
+    uint32_t* __restrict__ stage = topk_stage + (size_t)w * 2 * k;
+    const int64_t first = ((int64_t)blockIdx.x * (blockDim.x / kWave) + w) * rows_per_wave;
+    if (first >= N) return;
+    const int n = (int)(N - first < rows_per_wave ? N - first : rows_per_wave);  // rows of this wavefront
+    const float* __restrict__ h0 = H + first * (int64_t)dim;
+    value_store_t<VT>* __restrict__ od0 = sp_data + first * (int64_t)k;
+    IdxT* __restrict__ oi0 = sp_index + first * (int64_t)k;
+
+    // Three register buffers take turns (no copies: a copy would have to wait for the newest load).  Every turn
+    // issues exactly one row load - past the wavefront's last row it re-reads that row - so that the number of
+    // memory operations in flight is the same on every path and the waits can be exact.
+    float a[E], b[E], c[E];
+#define MAXK_TOPK_LOAD(buf, i) load_row<E, V>(h0 + (size_t)((i) < n ? (i) : n - 1) * dim, dim, lane, buf)
+#define MAXK_TOPK_SELECT(buf, i) \
+    select_row<E, V, PAD, VT, IdxT>(buf, dim, k, lane, stage, od0 + (size_t)(i) * k, oi0 + (size_t)(i) * k)
+    MAXK_TOPK_LOAD(a, 0);
+    MAXK_TOPK_LOAD(b, 1);
+    for (int i = 0; i < n; i += 3) {
+        MAXK_TOPK_LOAD(c, i + 2);
+        MAXK_TOPK_SELECT(a, i);
+        if (i + 1 >= n) break;
+        MAXK_TOPK_LOAD(a, i + 3);
+        MAXK_TOPK_SELECT(b, i + 1);
+        if (i + 2 >= n) break;
+        MAXK_TOPK_LOAD(b, i + 4);
+        MAXK_TOPK_SELECT(c, i + 2);
+    }
+#undef MAXK_TOPK_LOAD
+#undef MAXK_TOPK_SELECT
 }
 
 // MaxK backward: dense[row, sp_index[row,t]] = values[row,t], zeros elsewhere.  One wavefront per row;
@@ -178,16 +299,24 @@ template <int E, int V, int VT>
 maxk_status launch_v(const float* H, int64_t N, int dim, int k, void* sp_data, void* sp_index, int index_bytes,
                      hipStream_t s)
 {
-    const int rows_per_block = 4;
+    const int waves_per_block = 4;
+    // rows per wavefront: up to 8, fewer when that would leave CUs without work (256 CUs x 32 wavefronts)
+    int rows_per_wave = (int)std::min<int64_t>(8, std::max<int64_t>(1, N / (256 * 32)));
+    const int64_t rows_per_block = (int64_t)waves_per_block * rows_per_wave;
     const int64_t blocks = (N + rows_per_block - 1) / rows_per_block;
     if (blocks > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
-    dim3 grid((unsigned)blocks), block(rows_per_block * kWave);
+    dim3 grid((unsigned)blocks), block(waves_per_block * kWave);
+    const size_t lds = sizeof(uint32_t) * 2 * (size_t)k * waves_per_block;  // k <= dim <= MAXK_MAX_DIM: at most 32 KiB
     auto* od = (value_store_t<VT>*)sp_data;
+#define MAXK_TOPK_LAUNCH(PAD, IDX) \
+    hipLaunchKernelGGL((topk_cbsr_kernel<E, V, PAD, VT, IDX>), grid, block, lds, s, H, N, dim, k, rows_per_wave, od, (IDX*)sp_index)
+    const bool pad = dim != E * kWave;
     switch (index_bytes) {
-        case 1: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, VT, uint8_t>), grid, block, 0, s, H, N, dim, k, od, (uint8_t*)sp_index); break;
-        case 2: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, VT, uint16_t>), grid, block, 0, s, H, N, dim, k, od, (uint16_t*)sp_index); break;
-        default: hipLaunchKernelGGL((topk_cbsr_kernel<E, V, VT, int32_t>), grid, block, 0, s, H, N, dim, k, od, (int32_t*)sp_index); break;
+        case 1: if (pad) MAXK_TOPK_LAUNCH(true, uint8_t); else MAXK_TOPK_LAUNCH(false, uint8_t); break;
+        case 2: if (pad) MAXK_TOPK_LAUNCH(true, uint16_t); else MAXK_TOPK_LAUNCH(false, uint16_t); break;
+        default: if (pad) MAXK_TOPK_LAUNCH(true, int32_t); else MAXK_TOPK_LAUNCH(false, int32_t); break;
     }
+#undef MAXK_TOPK_LAUNCH
     MAXK_LAUNCH_CHECK();
     return MAXK_OK;
 }
