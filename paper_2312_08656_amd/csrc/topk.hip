@@ -50,19 +50,21 @@ __device__ __forceinline__ int column_of(int lane, int e)
 // then lane 15 of each row into the next row and lane 31 into the upper half; lane 63 ends up with the result.
 __device__ __forceinline__ uint32_t wave_max_nonneg(float x)
 {
-    auto step = [](float v, auto ctrl, auto rows) {
-        const int moved = __builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), decltype(ctrl)::value,
-                                                      decltype(rows)::value, 0xF, true);
-        return fmaxf(v, __uint_as_float((uint32_t)moved));
+    // bit patterns of non-negative floats order like unsigned integers
+    auto step = [](uint32_t v, auto ctrl, auto rows) {
+        const uint32_t moved = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, decltype(ctrl)::value,
+                                                                     decltype(rows)::value, 0xF, true);
+        return v > moved ? v : moved;
     };
     using std::integral_constant;
-    x = step(x, integral_constant<int, 0x111>{}, integral_constant<int, 0xF>{});  // row_shr:1
-    x = step(x, integral_constant<int, 0x112>{}, integral_constant<int, 0xF>{});  // row_shr:2
-    x = step(x, integral_constant<int, 0x114>{}, integral_constant<int, 0xF>{});  // row_shr:4
-    x = step(x, integral_constant<int, 0x118>{}, integral_constant<int, 0xF>{});  // row_shr:8
-    x = step(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});  // row_bcast:15 into rows 1 and 3
-    x = step(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});  // row_bcast:31 into rows 2 and 3
-    return (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(x), 63);
+    uint32_t b = __float_as_uint(x);
+    b = step(b, integral_constant<int, 0x111>{}, integral_constant<int, 0xF>{});  // row_shr:1
+    b = step(b, integral_constant<int, 0x112>{}, integral_constant<int, 0xF>{});  // row_shr:2
+    b = step(b, integral_constant<int, 0x114>{}, integral_constant<int, 0xF>{});  // row_shr:4
+    b = step(b, integral_constant<int, 0x118>{}, integral_constant<int, 0xF>{});  // row_shr:8
+    b = step(b, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});  // row_bcast:15 into rows 1 and 3
+    b = step(b, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});  // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)b, 63);
 }
 
 // pos[e] = number of flagged elements that precede (lane, e) in column order
@@ -118,8 +120,41 @@ __device__ __forceinline__ void load_row(const float* __restrict__ h, int dim, i
     }
 }
 
-// Selection and CBSR packing of one row held in registers.  `stage` is this wavefront's own LDS area of 2*k words:
-// the survivors are put there in CBSR order and leave as whole-row stores.
+// CBSR packing of the selected entries of one row.  `stage` is this wavefront's own LDS area of 2*k + 64 words: the
+// survivors are put there in CBSR order (value bits in [0, k), columns in [k, 2k)) and leave as whole-row stores, the
+// t-th survivor by lane t.  Entries that are not selected are written to word 2k + lane, which nobody reads, so
+// that no branch surrounds the LDS writes.  LDS operations of one wavefront execute in program order, so no barrier
+// is needed inside the wavefront.
+template <int E, int V, int VT, typename IdxT>
+__device__ __forceinline__ void write_row(const bool (&sel)[E], const float (&v)[E], int k, int lane,
+                                          uint32_t* __restrict__ stage, value_store_t<VT>* __restrict__ od,
+                                          IdxT* __restrict__ oi)
+{
+    int pos[E];
+    column_order_prefix<E, V>(sel, pos);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        stage[sel[e] ? pos[e] : 2 * k + lane] = __float_as_uint(v[e]);
+        stage[sel[e] ? k + pos[e] : 2 * k + lane] = (uint32_t)column_of<V>(lane, e);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (k <= kWave) {  // one store of each kind: the usual case, and a fixed number of memory operations
+        if (lane < k) {
+            od[lane] = narrow_value<VT>(__uint_as_float(stage[lane]));
+            oi[lane] = (IdxT)stage[k + lane];
+        }
+    } else {
+        for (int t = lane; t < k; t += kWave) {
+            od[t] = narrow_value<VT>(__uint_as_float(stage[t]));
+            oi[t] = (IdxT)stage[k + t];
+        }
+    }
+    __builtin_amdgcn_wave_barrier();  // the next row's survivors go to the same area
+}
+
+// Selection and CBSR packing of one row held in registers.  `stage` is this wavefront's own LDS area (see write_row).
 // VT: storage format of the values written (MAXK_VALUE_*); selection always works on the fp32 input
 // PAD: the row is shorter than the E*64 columns the lanes cover
 template <int E, int V, bool PAD, int VT, typename IdxT>
@@ -137,24 +172,26 @@ __device__ __forceinline__ void select_row(const float (&raw)[E], int dim, int k
         amax = fmaxf(amax, in ? fabsf(raw[e]) : 0.f);
     }
 
-    // Stage 1: bisection of a pivot on the value axis.  count(x >= lo) > k > count(x >= hi) is kept until a pivot
-    // keeps exactly k.  Everything but the compares is wave-uniform; readfirstlane tells the compiler so, which
-    // keeps the bounds, the pivot and the counts in scalar registers (E vector compares per step).
+    // Stage 1: bisection of a pivot on the value axis, pivot = 0 first, then +- max|x| / 2, / 4, ... until a pivot keeps
+    // exactly k.  The counts are scalar (ballot + scalar popcount).  The pivot and the step are the same in every
+    // lane but are kept in vector registers (the empty asm hides that they are uniform): the compares read them
+    // there, and a scalar copy would cost a move and wait states between dependent vector and scalar instructions
+    // on every step.  The scalar unit's issue rate is what bounds this kernel.
     const uint32_t amax_bits = wave_max_nonneg(amax);
     float pivot = 0.f;
     int kept = -1;  // entries the last pivot keeps
     if (amax_bits < 0x7F800000u && k < dim) {  // finite row (k = dim: every pivot above -max|x| keeps too few)
-        uint32_t lo = amax_bits | 0x80000000u, hi = amax_bits;
+        float half = 0.5f * __uint_as_float(amax_bits);
+        asm volatile("" : "+v"(pivot), "+v"(half));
         for (int step = 0; step < kPivotSteps; ++step) {
-            const float mid = 0.5f * __uint_as_float(lo) + 0.5f * __uint_as_float(hi);
-            const uint32_t mid_bits = (uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(mid));
-            pivot = __uint_as_float(mid_bits);
             int cnt = 0;
 #pragma unroll
             for (int e = 0; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[e] >= pivot));
-            kept = __builtin_amdgcn_readfirstlane(cnt);
+            kept = cnt;
             if (kept == k) break;
-            if (kept > k) lo = mid_bits; else hi = mid_bits;
+            const uint32_t down = kept > k ? 0u : 0x80000000u;  // too few kept: move the pivot down
+            pivot += __uint_as_float(__float_as_uint(half) ^ down);
+            half *= 0.5f;
         }
     }
 
@@ -162,7 +199,10 @@ __device__ __forceinline__ void select_row(const float (&raw)[E], int dim, int k
     if (kept == k) {
 #pragma unroll
         for (int e = 0; e < E; ++e) sel[e] = v[e] >= pivot;
-    } else {
+        write_row<E, V, VT, IdxT>(sel, v, k, lane, stage, od, oi);
+        return;
+    }
+    {
         // Stage 2 (rows without such a pivot within kPivotSteps): k-th largest key by MSB-first descent;
         // `exact` = the prefix already keeps exactly k.  Padding columns get key 0, below every non-NaN key.
         uint32_t key[E];
@@ -203,32 +243,7 @@ __device__ __forceinline__ void select_row(const float (&raw)[E], int dim, int k
         }
     }
 
-    int pos[E];
-    column_order_prefix<E, V>(sel, pos);
-    // survivors -> LDS in CBSR order (value bits, then column), then whole-row stores: t-th survivor by lane t.
-    // LDS operations of one wavefront execute in program order, so no barrier is needed inside the wavefront.
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        if (sel[e]) {
-            stage[pos[e]] = __float_as_uint(v[e]);
-            stage[k + pos[e]] = (uint32_t)column_of<V>(lane, e);
-        }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    if (k <= kWave) {  // one store of each kind: the usual case, and a fixed number of memory operations
-        if (lane < k) {
-            od[lane] = narrow_value<VT>(__uint_as_float(stage[lane]));
-            oi[lane] = (IdxT)stage[k + lane];
-        }
-    } else {
-        for (int t = lane; t < k; t += kWave) {
-            od[t] = narrow_value<VT>(__uint_as_float(stage[t]));
-            oi[t] = (IdxT)stage[k + t];
-        }
-    }
-    __builtin_amdgcn_wave_barrier();  // the next row's survivors go to the same area
+    write_row<E, V, VT, IdxT>(sel, v, k, lane, stage, od, oi);
 }
 
 // One wavefront owns `rows_per_wave` consecutive rows and keeps the loads of the next two rows in flight while it
@@ -239,10 +254,10 @@ __global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict_
                                                         int rows_per_wave, value_store_t<VT>* __restrict__ sp_data,
                                                         IdxT* __restrict__ sp_index)
 {
-    extern __shared__ uint32_t topk_stage[];  // 2*k words per wavefront
+    extern __shared__ uint32_t topk_stage[];  // 2*k + 64 words per wavefront
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform: rows and loop are scalar
-    uint32_t* __restrict__ stage = topk_stage + (size_t)w * 2 * k;
+    uint32_t* __restrict__ stage = topk_stage + w * (2 * k + kWave);
     const int64_t first = ((int64_t)blockIdx.x * (blockDim.x / kWave) + w) * rows_per_wave;
     if (first >= N) return;
     const int n = (int)(N - first < rows_per_wave ? N - first : rows_per_wave);  // rows of this wavefront
@@ -254,9 +269,10 @@ __global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict_
     // issues exactly one row load - past the wavefront's last row it re-reads that row - so that the number of
     // memory operations in flight is the same on every path and the waits can be exact.
     float a[E], b[E], c[E];
-#define MAXK_TOPK_LOAD(buf, i) load_row<E, V>(h0 + (size_t)((i) < n ? (i) : n - 1) * dim, dim, lane, buf)
+    // rows_per_wave * dim and rows_per_wave * k fit 32 bits (at most 8 rows of at most MAXK_MAX_DIM columns)
+#define MAXK_TOPK_LOAD(buf, i) load_row<E, V>(h0 + ((i) < n ? (i) : n - 1) * dim, dim, lane, buf)
 #define MAXK_TOPK_SELECT(buf, i) \
-    select_row<E, V, PAD, VT, IdxT>(buf, dim, k, lane, stage, od0 + (size_t)(i) * k, oi0 + (size_t)(i) * k)
+    select_row<E, V, PAD, VT, IdxT>(buf, dim, k, lane, stage, od0 + (i) * k, oi0 + (i) * k)
     MAXK_TOPK_LOAD(a, 0);
     MAXK_TOPK_LOAD(b, 1);
     for (int i = 0; i < n; i += 3) {
@@ -306,7 +322,7 @@ maxk_status launch_v(const float* H, int64_t N, int dim, int k, void* sp_data, v
     const int64_t blocks = (N + rows_per_block - 1) / rows_per_block;
     if (blocks > 0x7FFFFFFF) return MAXK_UNSUPPORTED;
     dim3 grid((unsigned)blocks), block(waves_per_block * kWave);
-    const size_t lds = sizeof(uint32_t) * 2 * (size_t)k * waves_per_block;  // k <= dim <= MAXK_MAX_DIM: at most 32 KiB
+    const size_t lds = sizeof(uint32_t) * (2 * (size_t)k + kWave) * waves_per_block;  // k <= MAXK_MAX_DIM: at most 33 KiB
     auto* od = (value_store_t<VT>*)sp_data;
 #define MAXK_TOPK_LAUNCH(PAD, IDX) \
     hipLaunchKernelGGL((topk_cbsr_kernel<E, V, PAD, VT, IDX>), grid, block, lds, s, H, N, dim, k, rows_per_wave, od, (IDX*)sp_index)
