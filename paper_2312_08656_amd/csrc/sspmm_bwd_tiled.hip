@@ -421,8 +421,14 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         const char* ext_at = reinterpret_cast<const char*>(a.extra1) + (int64_t)first * set_bytes;   // set whose columns are fetched
         const char* const idx_at = reinterpret_cast<const char*>(a.sp_index) + dest0 * k * (int64_t)sizeof(IdxT);
         const uint32_t idx_lane = (uint32_t)q * (uint32_t)(PPL * sizeof(IdxT));
-        char* const acc_lane = reinterpret_cast<char*>(acc) + q * (4 * PPL);
-        const char* const rows_b = reinterpret_cast<const char*>(rows);
+        // LDS addresses are worked out as 32-bit numbers ahead of the barrier and used as they are after it
+        typedef __attribute__((address_space(3))) char lds_char;
+        typedef __attribute__((address_space(3))) float lds_float;
+        typedef float vec4 __attribute__((ext_vector_type(4)));  // a plain vector type: it can be read through an LDS pointer
+        typedef __attribute__((address_space(3))) vec4 lds_vec4;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)lds;
+        const uint32_t acc_lane_off = lds0 + (uint32_t)q * (uint32_t)(4 * PPL);  // the accumulators come first
+        const uint32_t rows_off = lds0 + (uint32_t)acc_floats * 4u;
         const uint32_t row_bytes = (uint32_t)dim * 4u, buf_bytes = TR * row_bytes;
         __syncthreads();  // barrier t0: the rows of tile t0 are in buffer t0 & 1
 
@@ -447,49 +453,75 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
             xq0 = xq1 = xq2 = xq3 = make_uint2(0u, 0u);
             MAXK_TILED_FETCH_IDX(rq0, iq0, xq0) MAXK_TILED_FETCH_IDX(rq1, iq1, xq1)
             MAXK_TILED_FETCH_IDX(rq2, iq2, xq2) MAXK_TILED_FETCH_IDX(rq3, iq3, xq3)
-#define MAXK_TILED_ADD(V, SRCROW)                                                                   \
-    {                                                                                               \
-        const char* const row = buf + __umul24((SRCROW), row_bytes);                                \
-        const float v = (V);                                                                        \
-        _Pragma("unroll") for (int n = 0; n < NQ; ++n) {                                            \
-            av[n].x += v * *reinterpret_cast<const float*>(row + cb[4 * n]);                        \
-            av[n].y += v * *reinterpret_cast<const float*>(row + cb[4 * n + 1]);                    \
-            av[n].z += v * *reinterpret_cast<const float*>(row + cb[4 * n + 2]);                    \
-            av[n].w += v * *reinterpret_cast<const float*>(row + cb[4 * n + 3]);                    \
-        }                                                                                           \
+            // One set.  What a wavefront does between leaving a barrier and reaching the next one is on the critical
+            // path of that tile, so as much as possible is done in tiles where the wavefront has no set of its own
+            // (its sets are eight apart in the list, a tile holds about four): it first crosses into the tile BEFORE
+            // the set's tile, there takes the oldest queue entries, refills the queues (the same loads every time, so
+            // that the compiler can count them) and works out every LDS address - pinned in registers by the empty asm
+            // statements, which the compiler may not move across the barrier - and only then crosses into the set's
+            // tile, where nothing is left but LDS reads, multiply-adds and the LDS write.
+#define MAXK_TILED_PIN(X) asm volatile("" : "+v"(X));
+#define MAXK_TILED_CROSS                                                         \
+    {                                                                            \
+        ++tile;                                                                  \
+        s_end = s_end_next;                                                      \
+        __syncthreads();                                                         \
+        s_end_next = *dt_next++; /* asked for after the barrier */               \
     }
-            // one set: take the oldest queue entries, refill the queues (the same loads every time, so that the
-            // compiler can count them), cross into the set's tile, accumulate
 #define MAXK_TILED_SET(RQ, RQ_AHEAD, IQ, XQ, IT)                                                                      \
     {                                                                                                                 \
+        const uint32_t my_set = first + (uint32_t)(IT) * kAccWaves;                                                   \
+        while (my_set >= s_end_next) MAXK_TILED_CROSS /* now the set is in this tile or the next one */               \
         const uint2 cur = RQ;                                                                                         \
         const IdxVec<IdxT, PPL> ci = IQ;                                                                              \
         const uint2 cx = XQ;                                                                                          \
         MAXK_TILED_FETCH_REC(RQ)                                                                                      \
         MAXK_TILED_FETCH_IDX(RQ_AHEAD, IQ, XQ)                                                                        \
-        while (first + (uint32_t)(IT) * kAccWaves >= s_end) { /* next tile: everyone meets at one barrier per tile */ \
-            ++tile;                                                                                                   \
-            s_end = s_end_next;                                                                                       \
-            __syncthreads();                                                                                          \
-            s_end_next = *dt_next++; /* asked for after the barrier, needed at the next one */                        \
+        const bool cross = my_set >= s_end;                                                                           \
+        const bool live = lane_on && !(cur.y & kVisitNull);                                                           \
+        const bool two = live && (cur.y & kVisitHasExtra) != 0u;                                                      \
+        uint32_t acc_at = acc_lane_off + (cur.y & kVisitAccMask) * (uint32_t)(4 * PPL);                               \
+        const uint32_t buf_at = rows_off + (((uint32_t)tile + (cross ? 1u : 0u)) & 1u) * buf_bytes;                   \
+        const uint32_t row1 = buf_at + __umul24((cur.y >> kVisitSrcShift) & 63u, row_bytes);                          \
+        const uint32_t row2 = buf_at + __umul24(cx.y & 63u, row_bytes);                                               \
+        float w1 = __uint_as_float(cur.x), w2 = two ? __uint_as_float(cx.x) : 0.f; /* no second entry: slot unset */  \
+        uint32_t at1[PPL], at2[PPL]; /* LDS byte addresses of the sampled elements */                                 \
+        _Pragma("unroll") for (int i = 0; i < PPL; ++i) {                                                             \
+            at1[i] = row1 + ci.get(i) * 4u;                                                                           \
+            at2[i] = row2 + ci.get(i) * 4u;                                                                           \
+            MAXK_TILED_PIN(at1[i]) MAXK_TILED_PIN(at2[i])                                                             \
         }                                                                                                             \
-        if (lane_on && !(cur.y & kVisitNull)) {                                                                       \
-            const char* const buf = rows_b + (tile & 1) * buf_bytes;                                                  \
-            float4* const ap = reinterpret_cast<float4*>(acc_lane + (cur.y & kVisitAccMask) * (uint32_t)(4 * PPL));   \
-            float4 av[NQ];                                                                                            \
-            uint32_t cb[PPL]; /* byte offsets of the lane's columns within a row */                                   \
+        MAXK_TILED_PIN(acc_at) MAXK_TILED_PIN(w1) MAXK_TILED_PIN(w2)                                                  \
+        if (cross) MAXK_TILED_CROSS                                                                                   \
+        if (live) {                                                                                                   \
+            lds_vec4* const ap = (lds_vec4*)(uintptr_t)acc_at;                                                        \
+            vec4 av[NQ];                                                                                              \
+            float x1[PPL], x2[PPL];                                                                                   \
             _Pragma("unroll") for (int n = 0; n < NQ; ++n) av[n] = ap[n];                                             \
-            _Pragma("unroll") for (int i = 0; i < PPL; ++i) cb[i] = ci.get(i) * 4u;                                   \
-            MAXK_TILED_ADD(__uint_as_float(cur.x), (cur.y >> kVisitSrcShift) & 63u)                                   \
-            if (cur.y & kVisitHasExtra) {                                                                             \
-                MAXK_TILED_ADD(__uint_as_float(cx.x), cx.y & 63u)                                                     \
-                if (cx.y & kExtraMore) {                                                                              \
-                    uint32_t at = (cx.y >> kExtraNextShift) & 0x1FFFFFFu;                                             \
-                    for (;;) {                                                                                        \
-                        const uint2 e = a.chain[at++];                                                                \
-                        MAXK_TILED_ADD(__uint_as_float(e.x), e.y & 63u)                                               \
-                        if (!(e.y & kExtraMore)) break;                                                               \
+            _Pragma("unroll") for (int i = 0; i < PPL; ++i) x1[i] = *(const lds_float*)(uintptr_t)at1[i];             \
+            _Pragma("unroll") for (int i = 0; i < PPL; ++i) x2[i] = 0.f;                                              \
+            if (two) {                                                                                                \
+                _Pragma("unroll") for (int i = 0; i < PPL; ++i) x2[i] = *(const lds_float*)(uintptr_t)at2[i];         \
+            }                                                                                                         \
+            _Pragma("unroll") for (int n = 0; n < NQ; ++n) {                                                          \
+                av[n].x += w1 * x1[4 * n] + w2 * x2[4 * n];                                                           \
+                av[n].y += w1 * x1[4 * n + 1] + w2 * x2[4 * n + 1];                                                   \
+                av[n].z += w1 * x1[4 * n + 2] + w2 * x2[4 * n + 2];                                                   \
+                av[n].w += w1 * x1[4 * n + 3] + w2 * x2[4 * n + 3];                                                   \
+            }                                                                                                         \
+            if (two && (cx.y & kExtraMore)) {                                                                         \
+                uint32_t at = (cx.y >> kExtraNextShift) & 0x1FFFFFFu;                                                 \
+                for (;;) {                                                                                            \
+                    const uint2 e = a.chain[at++];                                                                    \
+                    const float v = __uint_as_float(e.x);                                                             \
+                    const uint32_t row = buf_at + __umul24(e.y & 63u, row_bytes);                                     \
+                    _Pragma("unroll") for (int n = 0; n < NQ; ++n) {                                                  \
+                        av[n].x += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n) * 4u);                      \
+                        av[n].y += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 1) * 4u);                  \
+                        av[n].z += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 2) * 4u);                  \
+                        av[n].w += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 3) * 4u);                  \
                     }                                                                                                 \
+                    if (!(e.y & kExtraMore)) break;                                                                   \
                 }                                                                                                     \
             }                                                                                                         \
             _Pragma("unroll") for (int n = 0; n < NQ; ++n) ap[n] = av[n];                                             \
@@ -516,7 +548,8 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
 #undef MAXK_TILED_FETCH_REC
 #undef MAXK_TILED_FETCH_IDX
 #undef MAXK_TILED_SET
-#undef MAXK_TILED_ADD
+#undef MAXK_TILED_CROSS
+#undef MAXK_TILED_PIN
         }
         while (tile < t1 - 1) {
             ++tile;
