@@ -121,6 +121,40 @@ def test_topk_ties_signed_zero_and_infinities():
             check_topk(Hw, k, sp_data, sp_index)
 
 
+@pytest.mark.parametrize("N", [1, 3, 8191, 8192 * 2 + 5, 8192 * 3 + 1, 8192 * 5 - 1, 8192 * 8 + 13, 70001])
+def test_topk_row_pipeline_edges_and_value_ranges(N):
+    """The top-k kernel gives a wavefront 1..8 consecutive rows (by N) and loads two rows ahead: sizes around every
+    rows-per-wavefront step with a ragged last wavefront, and rows whose values make the pivot bisection work hard
+    (huge and tiny magnitudes in one row, all-positive and all-negative rows, one outlier, nearly equal values)."""
+    rng = np.random.default_rng(N)
+    for dim, k, ib in ((256, 32, 1), (100, 7, 1), (384, 96, 2)):
+        H = synth.normal_matrix(N, dim, seed=N + dim)
+        n = min(N, 64)
+        rows = rng.choice(N, size=n, replace=False)
+        for i, r in enumerate(rows):
+            m = i % 8
+            if m == 0:
+                H[r] = np.abs(H[r]) + np.float32(1e-3)                 # all positive: the pivot never needs the lower half
+            elif m == 1:
+                H[r] = -np.abs(H[r]) - np.float32(1e-3)                # all negative
+            elif m == 2:
+                H[r] *= np.float32(1e-30)                              # tiny magnitudes
+                H[r, 0] = np.float32(3e38)                             # ... next to one huge outlier
+            elif m == 3:
+                H[r] = np.float32(1.0) + H[r] * np.float32(1e-6)       # nearly equal values (few distinct floats: ties)
+            elif m == 4:
+                H[r] = np.float32(1e-42) * rng.integers(-50, 50, dim).astype(np.float32)  # subnormals with ties
+            elif m == 5:
+                H[r] = np.float32(-3e38) + np.abs(H[r]) * np.float32(1e31)                # near -FLT_MAX
+            elif m == 6:
+                H[r] = np.exp(H[r] * np.float32(20.0)).astype(np.float32)                 # 17 orders of magnitude
+            else:
+                H[r] = np.float32(0.0)
+                H[r, dim - 1] = np.float32(-1.0)                       # zeros and one negative
+        sp_data, sp_index = gpu_topk(to_dev(H), k, ib)
+        check_topk(H, k, sp_data, sp_index)
+
+
 def test_empty_graph_empty_rows_duplicates_unsorted_columns():
     # N == 0
     z32 = torch.zeros(1, dtype=torch.int32, device="cuda")
