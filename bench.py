@@ -193,6 +193,9 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": dom_name, "device_kernel": dom_kernel, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": None if tr is None else tr["bytes"], "traffic_source": None if tr is None else tr["source"],
+                # measured L2<->fabric bytes per call / this run's time per call: how close the call is to the memory
+                # system's own limit, whatever the algorithmic count says
+                "traffic_rate_GBs": None if tr is None else round(tr["bytes"] / (dom_ms * 1e-3) / 1e9, 1),
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": round(dom_ms, 4)}
 
     if args.calibrate_copy:
