@@ -67,6 +67,7 @@ struct TiledSet {
     uint2* d_rec = nullptr;          // [total_sets * E] visit records (first entry inline)
     uint2* d_extra1 = nullptr;       // [total_sets * E] second entry of a visit
     uint2* d_chain = nullptr;        // [n_chain + 1] third and later entries
+    uint32_t* d_progress = nullptr;  // [8 * ceil(n_dsets / 8) * 32] progress marks of the running workgroups (pacing)
 };
 
 extern thread_local int32_t g_last_hip_error;
