@@ -7,20 +7,23 @@
 // through LDS in tiles of 16 rows with full, coalesced 16-byte loads.  A tile is used by every entry (i -> j) with i in
 // the tile and j in the set, so a row of dY is fetched once per destination set instead of once per entry:
 // (N / D) * N * dim * 4 bytes in all.  The sampled reads dY[i, sp_index[j, t]] and the read-add-write of the accumulators
-// are LDS traffic.  All workgroups of an XCD sweep the same source range at the same time, so the rows come from that
-// XCD's L2.
+// are LDS traffic.  The workgroups of an XCD that sweep the same source range (a "pack") are kept within a few dozen
+// tiles of each other by progress marks, so the rows come from that XCD's L2.
 //
-// Work assignment inside a workgroup (13 wavefronts):
-//   - wavefronts 8..11 only load: each keeps a register queue of the next four tiles' rows (plain 16-byte loads; the
+// Work assignment inside a workgroup (16 wavefronts):
+//   - wavefronts 11..14 only load: each keeps a register queue of the next four tiles' rows (plain 16-byte loads; the
 //     queue depth is what hides the L2 latency) and writes one tile per step into one of two LDS row buffers;
-//   - wavefronts 0..7 only accumulate.  A "visit" is one (tile, destination) pair with at least one entry; k/4 lanes
+//   - wavefronts 0..10 only accumulate.  A "visit" is one (tile, destination) pair with at least one entry; k/4 lanes
 //     work on it, four CBSR positions each, so a wave instruction covers a "set" of 64/(k/4) visits.  The visits of a
 //     tile have distinct destinations, so the sets of one tile can be worked on by different wavefronts at the same
-//     time without two lanes ever touching one accumulator; set s of the workgroup's list goes to wavefront s % 8,
+//     time without two lanes ever touching one accumulator; set s of the workgroup's list goes to wavefront s % 11,
 //     counted through the whole list, so each wavefront walks an arithmetic progression of sets and fetches its
-//     records eight sets ahead; a directory (one scalar load per tile) tells where a tile's sets end.
+//     records eight sets ahead; a directory (one scalar load per tile) tells where a tile's sets end.  Eleven, not
+//     eight: a tile holds about four sets, and a wavefront whose next set falls into the very next tile has to
+//     prepare it (records, LDS addresses) on that tile's critical path instead of in a tile of its own;
 //     A visit's first entry sits in the visit record, a second one in a parallel array, further ones (rare) in a chain;
-//   - wavefront 12 touches cache lines of the tiles further ahead so that they are in L2 when the loaders ask.
+//   - wavefront 15 touches cache lines of the tiles further ahead so that they are in L2 when the loaders ask, and
+//     paces the workgroup against the others of its pack.
 //   One workgroup barrier per tile hands a row buffer from the loaders to the accumulators and orders the
 //   accumulator updates of consecutive tiles.
 //
@@ -447,8 +450,8 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         // loads in flight (a vector load here would have to wait for all of them at every tile).
         typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
         const const_u32_ptr dt = (const_u32_ptr)(a.dir_sets + (int64_t)d * a.n_tiles);
-        // Set s of the workgroup's list goes to wavefront s % 8, whatever tile it belongs to: this wavefront's sets are
-        // first + 8 i, i = 0 .. n_it - 1
+        // Set s of the workgroup's list goes to wavefront s % kAccWaves, whatever tile it belongs to: this wavefront's
+        // sets are first + kAccWaves * i, i = 0 .. n_it - 1
         const uint32_t u0 = dt[t0], u1 = dt[t1];
         const uint32_t first = u0 + ((uint32_t)wave + (uint32_t)kAccWaves - u0 % (uint32_t)kAccWaves) % (uint32_t)kAccWaves;
         const int n_it = first >= u1 ? 0 : (int)((u1 - first + kAccWaves - 1) / kAccWaves);
@@ -498,7 +501,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
             MAXK_TILED_FETCH_IDX(rq2, iq2, xq2) MAXK_TILED_FETCH_IDX(rq3, iq3, xq3)
             // One set.  What a wavefront does between leaving a barrier and reaching the next one is on the critical
             // path of that tile, so as much as possible is done in tiles where the wavefront has no set of its own
-            // (its sets are eight apart in the list, a tile holds about four): it first crosses into the tile BEFORE
+            // (its sets are eleven apart in the list, a tile holds about four): it first crosses into the tile BEFORE
             // the set's tile, there takes the oldest queue entries, refills the queues (the same loads every time, so
             // that the compiler can count them) and works out every LDS address - pinned in registers by the empty asm
             // statements, which the compiler may not move across the barrier - and only then crosses into the set's
