@@ -65,8 +65,8 @@ struct TiledSet {
     int64_t total_sets = 0, n_visits = 0, n_chain = 0;
     uint32_t* d_dir_sets = nullptr;  // [n_dsets * n_tiles + 1 (+ spare)] first wave instruction of each list
     uint2* d_rec = nullptr;          // [total_sets * E] visit records (first entry inline)
-    uint2* d_extra1 = nullptr;       // [total_sets * E] second entry of a visit
-    uint2* d_chain = nullptr;        // [n_chain + 1] third and later entries
+    uint4* d_extra = nullptr;        // [total_sets * E] second and third entry of a visit
+    uint2* d_chain = nullptr;        // [n_chain + 1] fourth and later entries
     uint32_t* d_progress = nullptr;  // [8 * ceil(n_dsets / 8) * 32] progress marks of the running workgroups (pacing)
 };
 

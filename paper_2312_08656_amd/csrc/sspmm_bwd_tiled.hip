@@ -90,17 +90,15 @@ __global__ __launch_bounds__(256) void tiled_keys_kernel(const int32_t* __restri
     }
 }
 
-// head[p] = entry p opens a visit; third[p] = entry p is the third or a later one of its visit
+// head[p] = entry p opens a visit; late[p] = entry p is the fourth or a later one of its visit (it goes to the chain)
 __global__ __launch_bounds__(256) void tiled_flags_kernel(const uint64_t* __restrict__ key, int64_t nnz,
-                                                          uint32_t* __restrict__ head, uint32_t* __restrict__ third)
+                                                          uint32_t* __restrict__ head, uint32_t* __restrict__ late)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
         const uint64_t v = key[p] >> 6;
-        const bool h = p == 0 || (key[p - 1] >> 6) != v;
-        const bool h1 = p < 2 ? true : ((key[p - 2] >> 6) != v);  // p-1 opens the visit or belongs to another one
-        head[p] = h ? 1u : 0u;
-        third[p] = (!h && !h1) ? 1u : 0u;
+        head[p] = (p == 0 || (key[p - 1] >> 6) != v) ? 1u : 0u;
+        late[p] = (p >= 3 && (key[p - 3] >> 6) == v) ? 1u : 0u;  // sorted: then p-1 and p-2 are of this visit too
     }
 }
 
@@ -142,12 +140,12 @@ __global__ __launch_bounds__(256) void tiled_records_kernel(const uint64_t* __re
                                                             const float* __restrict__ val,
                                                             const uint32_t* __restrict__ head,
                                                             const uint32_t* __restrict__ rank,
-                                                            const uint32_t* __restrict__ third,
+                                                            const uint32_t* __restrict__ late,
                                                             const uint32_t* __restrict__ chain_pos, int64_t nnz,
                                                             int32_t E, int32_t LPV,
                                                             const uint32_t* __restrict__ first_visit,
                                                             const uint32_t* __restrict__ dir_sets,
-                                                            uint2* __restrict__ rec, uint2* __restrict__ extra1,
+                                                            uint2* __restrict__ rec, uint4* __restrict__ extra,
                                                             uint2* __restrict__ chain)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -164,11 +162,14 @@ __global__ __launch_bounds__(256) void tiled_records_kernel(const uint64_t* __re
                                    (jl * (uint32_t)LPV) | (il << kVisitSrcShift) | (more ? kVisitHasExtra : 0u));
             if (more) {
                 const bool more2 = p + 2 < nnz && !head[p + 2];
+                const bool more3 = more2 && p + 3 < nnz && !head[p + 3];
                 const uint32_t il1 = (uint32_t)(key[p + 1] & 63u);
-                extra1[slot] = make_uint2(__float_as_uint(val[p + 1]),
-                                          il1 | (more2 ? (kExtraMore | (chain_pos[p + 2] << kExtraNextShift)) : 0u));
+                const uint32_t il2 = more2 ? (uint32_t)(key[p + 2] & 63u) : 0u;
+                extra[slot] = make_uint4(__float_as_uint(val[p + 1]), il1 | (more2 ? kExtraMore : 0u),
+                                         more2 ? __float_as_uint(val[p + 2]) : 0u,
+                                         il2 | (more3 ? (kExtraMore | (chain_pos[p + 3] << kExtraNextShift)) : 0u));
             }
-        } else if (third[p]) {
+        } else if (late[p]) {
             chain[chain_pos[p]] = make_uint2(__float_as_uint(val[p]), il | (more ? kExtraMore : 0u));
         }
     }
@@ -182,8 +183,8 @@ struct TiledArgs {
     float* dXs;
     const uint32_t* dir_sets;  // [n_dsets * n_tiles + 1] first set of every (destination set, tile)
     const uint2* rec;          // [total_sets * E] visit records
-    const uint2* extra1;       // [total_sets * E] second entry of a visit, where it has one
-    const uint2* chain;        // third and later entries
+    const uint4* extra;        // [total_sets * E] second and third entry of a visit, where it has them
+    const uint2* chain;        // fourth and later entries
     int64_t N;
     int32_t dim, k;
     int32_t D, n_dsets, n_tiles;
@@ -464,7 +465,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         const int64_t step_bytes = set_bytes * kAccWaves;                       // from one of this wavefront's sets to the next
         const uint32_t rec_lane = (uint32_t)gs * 8u;
         const char* rec_at = reinterpret_cast<const char*>(a.rec) + (int64_t)first * set_bytes;      // set being fetched
-        const char* ext_at = reinterpret_cast<const char*>(a.extra1) + (int64_t)first * set_bytes;   // set whose columns are fetched
+        const char* ext_at = reinterpret_cast<const char*>(a.extra) + (int64_t)first * set_bytes * 2;  // set whose columns are fetched
         const char* const idx_at = reinterpret_cast<const char*>(a.sp_index) + dest0 * k * (int64_t)sizeof(IdxT);
         const uint32_t idx_lane = (uint32_t)q * (uint32_t)(PPL * sizeof(IdxT));
         // LDS addresses are worked out as 32-bit numbers ahead of the barrier and used as they are after it
@@ -482,7 +483,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
             static_assert(kRecAhead == 8 && kIdxAhead == 4, "the queues below are written out for these depths");
             uint2 rq0, rq1, rq2, rq3, rq4, rq5, rq6, rq7;  // named, not indexed: they must stay in registers
             IdxVec<IdxT, PPL> iq0, iq1, iq2, iq3;
-            uint2 xq0, xq1, xq2, xq3;
+            uint4 xq0, xq1, xq2, xq3;
             // the record arrays end with kRecAhead * 8 padding sets, so fetching ahead of the list needs no clamp
 #define MAXK_TILED_FETCH_REC(RQ)                                   \
     RQ = *reinterpret_cast<const uint2*>(rec_at + rec_lane);       \
@@ -492,11 +493,11 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
 // flight, and it would then wait for younger ones than it needs
 #define MAXK_TILED_FETCH_IDX(RQ, IQ, XQ)                                                                              \
     IQ.load(idx_at + ((RQ.y & kVisitAccMask) * (uint32_t)(PPL * sizeof(IdxT)) + idx_lane));                          \
-    XQ = *reinterpret_cast<const uint2*>(ext_at + ((RQ.y & kVisitHasExtra) ? rec_lane : 0u));                         \
-    ext_at += step_bytes;
+    XQ = *reinterpret_cast<const uint4*>(ext_at + ((RQ.y & kVisitHasExtra) ? 2u * rec_lane : 0u));                    \
+    ext_at += 2 * step_bytes;
             MAXK_TILED_FETCH_REC(rq0) MAXK_TILED_FETCH_REC(rq1) MAXK_TILED_FETCH_REC(rq2) MAXK_TILED_FETCH_REC(rq3)
             MAXK_TILED_FETCH_REC(rq4) MAXK_TILED_FETCH_REC(rq5) MAXK_TILED_FETCH_REC(rq6) MAXK_TILED_FETCH_REC(rq7)
-            xq0 = xq1 = xq2 = xq3 = make_uint2(0u, 0u);
+            xq0 = xq1 = xq2 = xq3 = make_uint4(0u, 0u, 0u, 0u);
             MAXK_TILED_FETCH_IDX(rq0, iq0, xq0) MAXK_TILED_FETCH_IDX(rq1, iq1, xq1)
             MAXK_TILED_FETCH_IDX(rq2, iq2, xq2) MAXK_TILED_FETCH_IDX(rq3, iq3, xq3)
             // One set.  What a wavefront does between leaving a barrier and reaching the next one is on the critical
@@ -520,7 +521,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         while (my_set >= s_end_next) MAXK_TILED_CROSS /* now the set is in this tile or the next one */               \
         const uint2 cur = RQ;                                                                                         \
         const IdxVec<IdxT, PPL> ci = IQ;                                                                              \
-        const uint2 cx = XQ;                                                                                          \
+        const uint4 cx = XQ;                                                                                          \
         MAXK_TILED_FETCH_REC(RQ)                                                                                      \
         MAXK_TILED_FETCH_IDX(RQ_AHEAD, IQ, XQ)                                                                        \
         const bool cross = my_set >= s_end;                                                                           \
@@ -555,8 +556,18 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
                 av[n].z += w1 * x1[4 * n + 2] + w2 * x2[4 * n + 2];                                                   \
                 av[n].w += w1 * x1[4 * n + 3] + w2 * x2[4 * n + 3];                                                   \
             }                                                                                                         \
-            if (two && (cx.y & kExtraMore)) {                                                                         \
-                uint32_t at = (cx.y >> kExtraNextShift) & 0x1FFFFFFu;                                                 \
+            if (two && (cx.y & kExtraMore)) { /* a third entry, from the same slot (2 visits in 1000 on the dense workload) */ \
+                const float v = __uint_as_float(cx.z);                                                                \
+                const uint32_t row = buf_at + __umul24(cx.w & 63u, row_bytes);                                        \
+                _Pragma("unroll") for (int n = 0; n < NQ; ++n) {                                                      \
+                    av[n].x += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n) * 4u);                          \
+                    av[n].y += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 1) * 4u);                      \
+                    av[n].z += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 2) * 4u);                      \
+                    av[n].w += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 3) * 4u);                      \
+                }                                                                                                     \
+            }                                                                                                         \
+            if (two && (cx.y & kExtraMore) && (cx.w & kExtraMore)) { /* fourth and later: a dependent load each */    \
+                uint32_t at = (cx.w >> kExtraNextShift) & 0x1FFFFFFu;                                                 \
                 for (;;) {                                                                                            \
                     const uint2 e = a.chain[at++];                                                                    \
                     const float v = __uint_as_float(e.x);                                                             \
@@ -639,7 +650,7 @@ void free_tiled(TiledSet& T)
 {
     (void)hipFree(T.d_dir_sets);
     (void)hipFree(T.d_rec);
-    (void)hipFree(T.d_extra1);
+    (void)hipFree(T.d_extra);
     (void)hipFree(T.d_chain);
     (void)hipFree(T.d_progress);
     T = TiledSet();
@@ -678,12 +689,12 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
     hipStream_t s = nullptr;
     uint64_t *d_key = nullptr, *d_key_sorted = nullptr;
     float* d_val_sorted = nullptr;
-    uint32_t *d_head = nullptr, *d_rank = nullptr, *d_third = nullptr, *d_chain_pos = nullptr, *d_first_visit = nullptr,
+    uint32_t *d_head = nullptr, *d_rank = nullptr, *d_late = nullptr, *d_chain_pos = nullptr, *d_first_visit = nullptr,
              *d_sets = nullptr;
     void* d_tmp = nullptr;
     auto cleanup = [&]() {
         (void)hipFree(d_key); (void)hipFree(d_key_sorted); (void)hipFree(d_val_sorted); (void)hipFree(d_head);
-        (void)hipFree(d_rank); (void)hipFree(d_third); (void)hipFree(d_chain_pos); (void)hipFree(d_first_visit);
+        (void)hipFree(d_rank); (void)hipFree(d_late); (void)hipFree(d_chain_pos); (void)hipFree(d_first_visit);
         (void)hipFree(d_sets); (void)hipFree(d_tmp);
     };
 #define MAXK_TRY_CLEAN(expr)                                                           \
@@ -712,25 +723,25 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
 
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_head, sizeof(uint32_t) * (size_t)nnz));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_rank, sizeof(uint32_t) * (size_t)nnz));
-    MAXK_TRY_CLEAN(hipMalloc((void**)&d_third, sizeof(uint32_t) * (size_t)nnz));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_late, sizeof(uint32_t) * (size_t)nnz));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_chain_pos, sizeof(uint32_t) * (size_t)nnz));
-    hipLaunchKernelGGL(tiled_flags_kernel, dim3(blocks), dim3(256), 0, s, d_key_sorted, nnz, d_head, d_third);
+    hipLaunchKernelGGL(tiled_flags_kernel, dim3(blocks), dim3(256), 0, s, d_key_sorted, nnz, d_head, d_late);
     MAXK_TRY_CLEAN(hipGetLastError());
     tmp_bytes = 0;
     MAXK_TRY_CLEAN(rocprim::inclusive_scan(nullptr, tmp_bytes, d_head, d_rank, (size_t)nnz, rocprim::plus<uint32_t>(), s));
     size_t tmp2 = 0;
-    MAXK_TRY_CLEAN(rocprim::exclusive_scan(nullptr, tmp2, d_third, d_chain_pos, 0u, (size_t)nnz, rocprim::plus<uint32_t>(), s));
+    MAXK_TRY_CLEAN(rocprim::exclusive_scan(nullptr, tmp2, d_late, d_chain_pos, 0u, (size_t)nnz, rocprim::plus<uint32_t>(), s));
     tmp_bytes = std::max(tmp_bytes, tmp2);
     MAXK_TRY_CLEAN(hipMalloc(&d_tmp, tmp_bytes ? tmp_bytes : 16));
     MAXK_TRY_CLEAN(rocprim::inclusive_scan(d_tmp, tmp_bytes, d_head, d_rank, (size_t)nnz, rocprim::plus<uint32_t>(), s));
-    MAXK_TRY_CLEAN(rocprim::exclusive_scan(d_tmp, tmp2, d_third, d_chain_pos, 0u, (size_t)nnz, rocprim::plus<uint32_t>(), s));
-    uint32_t n_visits = 0, last_third = 0, last_chain = 0;
+    MAXK_TRY_CLEAN(rocprim::exclusive_scan(d_tmp, tmp2, d_late, d_chain_pos, 0u, (size_t)nnz, rocprim::plus<uint32_t>(), s));
+    uint32_t n_visits = 0, last_late = 0, last_chain = 0;
     MAXK_TRY_CLEAN(hipMemcpyAsync(&n_visits, d_rank + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, s));
-    MAXK_TRY_CLEAN(hipMemcpyAsync(&last_third, d_third + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    MAXK_TRY_CLEAN(hipMemcpyAsync(&last_late, d_late + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, s));
     MAXK_TRY_CLEAN(hipMemcpyAsync(&last_chain, d_chain_pos + (nnz - 1), sizeof(uint32_t), hipMemcpyDeviceToHost, s));
     MAXK_TRY_CLEAN(hipStreamSynchronize(s));
     (void)hipFree(d_tmp); d_tmp = nullptr;
-    const int64_t n_chain = (int64_t)last_chain + last_third;
+    const int64_t n_chain = (int64_t)last_chain + last_late;
     if (n_chain >= kMaxChain) { cleanup(); return MAXK_UNSUPPORTED; }
 
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_first_visit, sizeof(uint32_t) * (size_t)(n_groups + 1)));
@@ -757,13 +768,13 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
     // padding sets at the end: the kernel fetches kRecAhead of a wavefront's sets ahead without clamping
     const int64_t n_slots = ((int64_t)total_sets + (kRecAhead + 1) * kAccWaves) * E;
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_rec, sizeof(uint2) * (size_t)std::max<int64_t>(n_slots, 1)));
-    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_extra1, sizeof(uint2) * (size_t)std::max<int64_t>(n_slots, 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_extra, sizeof(uint4) * (size_t)std::max<int64_t>(n_slots, 1)));
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_chain, sizeof(uint2) * (size_t)(n_chain + 1)));
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_progress, sizeof(uint32_t) * (size_t)(kMaxUnits((int)n_dsets) * kMarkStride)));  // (T.n_dsets is set below)
     hipLaunchKernelGGL(tiled_fill_null_kernel, dim3((unsigned)std::min<int64_t>((n_slots + 255) / 256 + 1, 65536)), dim3(256),
                        0, s, T.d_rec, n_slots);
     hipLaunchKernelGGL(tiled_records_kernel, dim3(blocks), dim3(256), 0, s, d_key_sorted, d_val_sorted, d_head, d_rank,
-                       d_third, d_chain_pos, nnz, E, LPV, d_first_visit, T.d_dir_sets, T.d_rec, T.d_extra1, T.d_chain);
+                       d_late, d_chain_pos, nnz, E, LPV, d_first_visit, T.d_dir_sets, T.d_rec, T.d_extra, T.d_chain);
     MAXK_TRY_CLEAN(hipGetLastError());
     MAXK_TRY_CLEAN(hipStreamSynchronize(s));
 #undef MAXK_TRY_CLEAN
@@ -796,7 +807,7 @@ maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, 
     a.dXs = dXs;
     a.dir_sets = T.d_dir_sets;
     a.rec = T.d_rec;
-    a.extra1 = T.d_extra1;
+    a.extra = T.d_extra;
     a.chain = T.d_chain;
     a.N = N;
     a.dim = dim;
