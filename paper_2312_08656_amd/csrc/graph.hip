@@ -532,17 +532,17 @@ int auto_bwd_mode(const maxk_graph* g, int dim, int k, int val_bytes = 4, bool t
     const double per_line = 128.0 / val_bytes;  // dY elements per cache line
     const double lines = dim <= per_line ? 1.0 : (dim / per_line) * (1.0 - std::pow(1.0 - per_line / dim, (double)k));
     if (entries_per_visit >= 2.0 && n_slabs * (double)g->N < 1.8e19) {
-        // Dense neighbourhoods: slab pull or the LDS-tiled kernel, by cost models fitted on the dense workload (256 CUs):
-        // slab pull moves the cache lines that an entry's k columns touch (plus ~0.35 lines of streamed arrays) at
-        // ~5.6 ps per line, and pays ~10 us per slab launch; the tiled kernel pays ~270 ns per (destination set,
-        // tile) step on each CU and ~(7.1 + 0.41 k) ps per entry.  The tiled model runs up to 30 % low on graphs with
-        // heavier hubs than the one it was fitted on, the slab model within 10 %, so the tiled kernel has to win by 25 %.
+        // Dense neighbourhoods: slab pull or the LDS-tiled kernel, by cost models fitted on the dense and the
+        // ogbn-proteins-like workload (256 CUs): slab pull moves the cache lines that an entry's k columns touch (plus
+        // ~0.35 lines of streamed arrays) at ~5.2 ps per line, and pays ~10 us per slab launch; the tiled kernel pays
+        // ~150 ns per (destination set, tile) step on each CU and ~(3.0 + 0.73 k) ps per entry.  Both models are
+        // within 10 % of the measurements from k = 16 up (they run high at k = 8, where the choice is clear).
         TiledShape sh;
         if (tiled_ok && val_bytes == 4 && tiled_shape(g->N, dim, k, sh)) {
             const double n_tiles = std::ceil((double)g->N / sh.TR);
-            const double t_slab = (double)g->nnz * (lines + 0.35) * 5.6e-12 + n_slabs * 10e-6;
-            const double t_tiled = 270e-9 * sh.n_dsets * n_tiles / 256.0 + (double)g->nnz * (7.1e-12 + 0.41e-12 * k);
-            if (1.25 * t_tiled < t_slab && (double)sh.n_dsets * n_tiles < 2.6e8) return MAXK_BWD_TILED;
+            const double t_slab = (double)g->nnz * (lines + 0.35) * 5.2e-12 + n_slabs * 10e-6;
+            const double t_tiled = 150e-9 * sh.n_dsets * n_tiles / 256.0 + (double)g->nnz * (3.0e-12 + 0.73e-12 * k);
+            if (1.05 * t_tiled < t_slab && (double)sh.n_dsets * n_tiles < 2.6e8) return MAXK_BWD_TILED;
         }
         return MAXK_BWD_SLAB_PULL;
     }

@@ -47,7 +47,7 @@ def test_dense_graph_builds():
     assert info["nnz"] == synth.CONFIGS["dense"].nnz == 114_848_855
     assert 15_000 <= info["max_degree"] <= 25_000
     # dense neighbourhoods: the library's own choice is the LDS-tiled kernel at small k and the L2-tiled pull above
-    want = {8: "tiled", 16: "tiled", 32: "slab_pull", 64: "slab_pull", 96: "slab_pull", 128: "slab_pull"}
+    want = {8: "tiled", 16: "tiled", 32: "tiled", 64: "slab_pull", 96: "slab_pull", 128: "slab_pull"}
     assert {k: dg.handle.bwd_choice(256, k) for k in synth.CONFIGS["dense"].ks} == want
 
 
@@ -128,7 +128,7 @@ def test_proteins_like_every_element(k):
     dg, H, dY = _setup("proteins_like")
     assert dg.handle.info()["nnz"] == synth.CONFIGS["proteins_like"].nnz == 79_255_038
     say(f"  proteins_like k={k}: library's backward choice {dg.handle.bwd_choice(256, k)}")
-    assert dg.handle.bwd_choice(256, k) == {8: "tiled", 32: "slab_pull"}[k]  # the faster kernel by measurement
+    assert dg.handle.bwd_choice(256, k) == "tiled"  # the faster kernel by measurement at both k
     full_pass(dg, H, dY, k, 1, sampled=False, spmm=(k == 32), narrow=False)
 
 
