@@ -551,10 +551,10 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
                 _Pragma("unroll") for (int i = 0; i < PPL; ++i) x2[i] = *(const lds_float*)(uintptr_t)at2[i];         \
             }                                                                                                         \
             _Pragma("unroll") for (int n = 0; n < NQ; ++n) {                                                          \
-                av[n].x += w1 * x1[4 * n] + w2 * x2[4 * n];                                                           \
-                av[n].y += w1 * x1[4 * n + 1] + w2 * x2[4 * n + 1];                                                   \
-                av[n].z += w1 * x1[4 * n + 2] + w2 * x2[4 * n + 2];                                                   \
-                av[n].w += w1 * x1[4 * n + 3] + w2 * x2[4 * n + 3];                                                   \
+                av[n].x = fmaf(w2, x2[4 * n], fmaf(w1, x1[4 * n], av[n].x)); /* two multiply-adds per element */      \
+                av[n].y = fmaf(w2, x2[4 * n + 1], fmaf(w1, x1[4 * n + 1], av[n].y));                                  \
+                av[n].z = fmaf(w2, x2[4 * n + 2], fmaf(w1, x1[4 * n + 2], av[n].z));                                  \
+                av[n].w = fmaf(w2, x2[4 * n + 3], fmaf(w1, x1[4 * n + 3], av[n].w));                                  \
             }                                                                                                         \
             if (two && (cx.y & kExtraMore)) { /* a third entry, from the same slot (2 visits in 1000 on the dense workload) */ \
                 const float v = __uint_as_float(cx.z);                                                                \
