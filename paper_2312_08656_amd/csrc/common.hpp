@@ -66,7 +66,8 @@ struct TiledSet {
     uint32_t* d_dir_sets = nullptr;  // [n_dsets * n_tiles + 1 (+ spare)] first wave instruction of each list
     uint2* d_rec = nullptr;          // [total_sets * E] visit records (first entry inline)
     uint4* d_extra = nullptr;        // [total_sets * E] second and third entry of a visit
-    uint2* d_chain = nullptr;        // [n_chain + 1] fourth and later entries
+    uint4* d_ovf = nullptr;          // [n_chain + 1] fourth and later entries of a visit (added at the end of the kernel)
+    uint32_t* d_ovf_dir = nullptr;   // [n_dsets * n_tiles + 1] overflow entries before every (destination set, tile)
     uint32_t* d_progress = nullptr;  // [8 * ceil(n_dsets / 8) * 32] progress marks of the running workgroups (pacing)
 };
 

@@ -21,7 +21,8 @@
 //     records eight sets ahead; a directory (one scalar load per tile) tells where a tile's sets end.  Eleven, not
 //     eight: a tile holds about four sets, and a wavefront whose next set falls into the very next tile has to
 //     prepare it (records, LDS addresses) on that tile's critical path instead of in a tile of its own;
-//     A visit's first entry sits in the visit record, a second one in a parallel array, further ones (rare) in a chain;
+//     A visit's first entry sits in the visit record, the second and third in a parallel 16-byte slot; further ones
+//     (rare) are not worked on tile by tile at all: the workgroup adds them at the end, straight from dY;
 //   - wavefront 15 touches cache lines of the tiles further ahead so that they are in L2 when the loaders ask, and
 //     paces the workgroup against the others of its pack.
 //   One workgroup barrier per tile hands a row buffer from the loaders to the accumulators and orders the
@@ -64,8 +65,6 @@ constexpr uint32_t kVisitHasExtra = 1u << 20;
 constexpr uint32_t kVisitNull = 1u << 21;                // padding slot
 // second word of an extra entry: source row within the tile, chain position of the next one, "another one follows"
 constexpr uint32_t kExtraMore = 1u << 31;
-constexpr uint32_t kExtraNextShift = 6;                  // 25 bits
-constexpr int64_t kMaxChain = (int64_t)1 << 25;
 
 // ------------------------------------------------------------------ table build ----
 
@@ -102,12 +101,14 @@ __global__ __launch_bounds__(256) void tiled_flags_kernel(const uint64_t* __rest
     }
 }
 
-// sets[g] = wave instructions that the visits of group g need; first_visit[g] = visits before group g
+// sets[g] = wave instructions that the visits of group g need; first_visit[g] = visits before group g;
+// ovf_dir[g] = overflow entries (fourth and later entries of a visit) before group g
 __global__ __launch_bounds__(256) void tiled_groups_kernel(const uint64_t* __restrict__ key,
-                                                           const uint32_t* __restrict__ rank, int64_t nnz,
+                                                           const uint32_t* __restrict__ rank,
+                                                           const uint32_t* __restrict__ chain_pos, int64_t nnz,
                                                            int64_t n_groups, int32_t E, uint32_t n_visits,
-                                                           uint32_t* __restrict__ first_visit,
-                                                           uint32_t* __restrict__ sets)
+                                                           uint32_t n_ovf, uint32_t* __restrict__ first_visit,
+                                                           uint32_t* __restrict__ sets, uint32_t* __restrict__ ovf_dir)
 {
     const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (g > n_groups) return;
@@ -120,8 +121,10 @@ __global__ __launch_bounds__(256) void tiled_groups_kernel(const uint64_t* __res
         return lo;
     };
     auto visits_before = [&](int64_t pos) { return pos < nnz ? rank[pos] - 1u : n_visits; };
-    const uint32_t fv = visits_before(lower((uint64_t)g << 18));
+    const int64_t pos = lower((uint64_t)g << 18);
+    const uint32_t fv = visits_before(pos);
     first_visit[g] = fv;
+    ovf_dir[g] = pos < nnz ? chain_pos[pos] : n_ovf;
     if (g < n_groups) {
         const uint32_t nv = visits_before(lower((uint64_t)(g + 1) << 18)) - fv;
         sets[g] = (nv + (uint32_t)E - 1u) / (uint32_t)E;
@@ -142,18 +145,18 @@ __global__ __launch_bounds__(256) void tiled_records_kernel(const uint64_t* __re
                                                             const uint32_t* __restrict__ rank,
                                                             const uint32_t* __restrict__ late,
                                                             const uint32_t* __restrict__ chain_pos, int64_t nnz,
-                                                            int32_t E, int32_t LPV,
+                                                            int32_t E, int32_t LPV, int32_t n_tiles, int32_t tile_rows,
                                                             const uint32_t* __restrict__ first_visit,
                                                             const uint32_t* __restrict__ dir_sets,
                                                             uint2* __restrict__ rec, uint4* __restrict__ extra,
-                                                            uint2* __restrict__ chain)
+                                                            uint4* __restrict__ ovf)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
         const uint64_t kp = key[p];
         const uint32_t il = (uint32_t)(kp & 63u);
-        const bool more = p + 1 < nnz && !head[p + 1];
         if (head[p]) {
+            const bool more = p + 1 < nnz && !head[p + 1];
             const uint64_t g = kp >> 18;
             const uint32_t v = rank[p] - 1u;
             const int64_t slot = (int64_t)dir_sets[g] * E + (int64_t)(v - first_visit[g]);
@@ -162,15 +165,18 @@ __global__ __launch_bounds__(256) void tiled_records_kernel(const uint64_t* __re
                                    (jl * (uint32_t)LPV) | (il << kVisitSrcShift) | (more ? kVisitHasExtra : 0u));
             if (more) {
                 const bool more2 = p + 2 < nnz && !head[p + 2];
-                const bool more3 = more2 && p + 3 < nnz && !head[p + 3];
                 const uint32_t il1 = (uint32_t)(key[p + 1] & 63u);
                 const uint32_t il2 = more2 ? (uint32_t)(key[p + 2] & 63u) : 0u;
                 extra[slot] = make_uint4(__float_as_uint(val[p + 1]), il1 | (more2 ? kExtraMore : 0u),
                                          more2 ? __float_as_uint(val[p + 2]) : 0u,
-                                         il2 | (more3 ? (kExtraMore | (chain_pos[p + 3] << kExtraNextShift)) : 0u));
+                                         il2);
             }
         } else if (late[p]) {
-            chain[chain_pos[p]] = make_uint2(__float_as_uint(val[p]), il | (more ? kExtraMore : 0u));
+            // fourth and later entries of a visit (rare) are not worked on tile by tile: the kernel adds them at the end,
+            // straight from dY.  {weight, source row, destination within the set}
+            const uint32_t tile = (uint32_t)((kp >> 18) % (uint64_t)n_tiles);
+            ovf[chain_pos[p]] = make_uint4(__float_as_uint(val[p]), tile * (uint32_t)tile_rows + il,
+                                           (uint32_t)((kp >> 6) & 0xFFFu), 0u);
         }
     }
 }
@@ -184,7 +190,8 @@ struct TiledArgs {
     const uint32_t* dir_sets;  // [n_dsets * n_tiles + 1] first set of every (destination set, tile)
     const uint2* rec;          // [total_sets * E] visit records
     const uint4* extra;        // [total_sets * E] second and third entry of a visit, where it has them
-    const uint2* chain;        // fourth and later entries
+    const uint4* ovf;          // fourth and later entries of a visit: {weight, source row, destination within its set}
+    const uint32_t* ovf_dir;   // [n_dsets * n_tiles + 1] overflow entries before every (destination set, tile)
     int64_t N;
     int32_t dim, k;
     int32_t D, n_dsets, n_tiles;
@@ -566,21 +573,6 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
                     av[n].w += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 3) * 4u);                      \
                 }                                                                                                     \
             }                                                                                                         \
-            if (two && (cx.y & kExtraMore) && (cx.w & kExtraMore)) { /* fourth and later: a dependent load each */    \
-                uint32_t at = (cx.w >> kExtraNextShift) & 0x1FFFFFFu;                                                 \
-                for (;;) {                                                                                            \
-                    const uint2 e = a.chain[at++];                                                                    \
-                    const float v = __uint_as_float(e.x);                                                             \
-                    const uint32_t row = buf_at + __umul24(e.y & 63u, row_bytes);                                     \
-                    _Pragma("unroll") for (int n = 0; n < NQ; ++n) {                                                  \
-                        av[n].x += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n) * 4u);                      \
-                        av[n].y += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 1) * 4u);                  \
-                        av[n].z += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 2) * 4u);                  \
-                        av[n].w += v * *(const lds_float*)(uintptr_t)(row + ci.get(4 * n + 3) * 4u);                  \
-                    }                                                                                                 \
-                    if (!(e.y & kExtraMore)) break;                                                                   \
-                }                                                                                                     \
-            }                                                                                                         \
             _Pragma("unroll") for (int n = 0; n < NQ; ++n) ap[n] = av[n];                                             \
         }                                                                                                             \
     }
@@ -611,6 +603,39 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         while (tile < t1 - 1) {
             ++tile;
             __syncthreads();
+        }
+    }
+    __syncthreads();
+    {
+        // Overflow entries of this (source range, destination set): fourth and later entries of a visit.  They are few
+        // (1 visit in 7,000 on the dense workload has any), so they are not chained behind their visit, where the
+        // dependent load would sit on a tile's critical path, but added here: sampled straight from dY, with LDS
+        // atomics, since two of them may belong to one destination.  Same lane layout as a set: k/4 lanes per entry.
+        const int LPV = k / PPL, E = kWave / LPV, g = lane / LPV, q = lane - g * LPV;
+        const uint32_t o0 = a.ovf_dir[(int64_t)d * a.n_tiles + t0], o1 = a.ovf_dir[(int64_t)d * a.n_tiles + t1];
+        if (g < E && o0 < o1) {
+            // three stages in flight, so that an iteration waits for one round trip, not three: the record two
+            // iterations ahead, the destination's columns one ahead, the samples of the current one (reads past the
+            // end are clamped to the last entry and dropped)
+            const uint32_t stride = (uint32_t)((kTiledThreads / kWave) * E), last = o1 - 1;
+            const IdxT* const ib = reinterpret_cast<const IdxT*>(a.sp_index) + (dest0 * (int64_t)k + q * PPL);
+            uint32_t e = o0 + (uint32_t)(wave * E + g);
+            uint4 r0 = a.ovf[min(e, last)], r1 = a.ovf[min(e + stride, last)];
+            IdxVec<IdxT, PPL> i0;
+            i0.load(ib + (int64_t)r0.z * k);
+            for (; e < o1; e += stride) {
+                const uint4 r2 = a.ovf[min(e + 2 * stride, last)];
+                IdxVec<IdxT, PPL> i1;
+                i1.load(ib + (int64_t)r1.z * k);
+                const float w = __uint_as_float(r0.x);
+                const float* __restrict__ row = a.dY + (int64_t)r0.y * dim;
+                float x[PPL];
+#pragma unroll
+                for (int c = 0; c < PPL; ++c) x[c] = row[i0.get(c)];
+#pragma unroll
+                for (int c = 0; c < PPL; ++c) atomicAdd(&acc[r0.z * k + q * PPL + c], w * x[c]);
+                r0 = r1; r1 = r2; i0 = i1;
+            }
         }
     }
     __syncthreads();
@@ -651,7 +676,8 @@ void free_tiled(TiledSet& T)
     (void)hipFree(T.d_dir_sets);
     (void)hipFree(T.d_rec);
     (void)hipFree(T.d_extra);
-    (void)hipFree(T.d_chain);
+    (void)hipFree(T.d_ovf);
+    (void)hipFree(T.d_ovf_dir);
     (void)hipFree(T.d_progress);
     T = TiledSet();
 }
@@ -742,14 +768,15 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
     MAXK_TRY_CLEAN(hipStreamSynchronize(s));
     (void)hipFree(d_tmp); d_tmp = nullptr;
     const int64_t n_chain = (int64_t)last_chain + last_late;
-    if (n_chain >= kMaxChain) { cleanup(); return MAXK_UNSUPPORTED; }
 
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_first_visit, sizeof(uint32_t) * (size_t)(n_groups + 1)));
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_sets, sizeof(uint32_t) * (size_t)(n_groups + 1)));
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_dir_sets, sizeof(uint32_t) * (size_t)(n_groups + 4)));
     MAXK_TRY_CLEAN(hipMemsetAsync(T.d_dir_sets + n_groups, 0xFF, sizeof(uint32_t) * 4, s));  // spare entries: read, never used
+    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_ovf_dir, sizeof(uint32_t) * (size_t)(n_groups + 1)));
     hipLaunchKernelGGL(tiled_groups_kernel, dim3((unsigned)((n_groups + 1 + 255) / 256)), dim3(256), 0, s, d_key_sorted,
-                       d_rank, nnz, n_groups, E, n_visits, d_first_visit, d_sets);
+                       d_rank, d_chain_pos, nnz, n_groups, E, n_visits, (uint32_t)n_chain, d_first_visit, d_sets,
+                       T.d_ovf_dir);
     MAXK_TRY_CLEAN(hipGetLastError());
     tmp_bytes = 0;
     MAXK_TRY_CLEAN(rocprim::exclusive_scan(nullptr, tmp_bytes, d_sets, T.d_dir_sets, 0u, (size_t)(n_groups + 1),
@@ -769,12 +796,13 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
     const int64_t n_slots = ((int64_t)total_sets + (kRecAhead + 1) * kAccWaves) * E;
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_rec, sizeof(uint2) * (size_t)std::max<int64_t>(n_slots, 1)));
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_extra, sizeof(uint4) * (size_t)std::max<int64_t>(n_slots, 1)));
-    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_chain, sizeof(uint2) * (size_t)(n_chain + 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_ovf, sizeof(uint4) * (size_t)(n_chain + 1)));
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_progress, sizeof(uint32_t) * (size_t)(kMaxUnits((int)n_dsets) * kMarkStride)));  // (T.n_dsets is set below)
     hipLaunchKernelGGL(tiled_fill_null_kernel, dim3((unsigned)std::min<int64_t>((n_slots + 255) / 256 + 1, 65536)), dim3(256),
                        0, s, T.d_rec, n_slots);
     hipLaunchKernelGGL(tiled_records_kernel, dim3(blocks), dim3(256), 0, s, d_key_sorted, d_val_sorted, d_head, d_rank,
-                       d_late, d_chain_pos, nnz, E, LPV, d_first_visit, T.d_dir_sets, T.d_rec, T.d_extra, T.d_chain);
+                       d_late, d_chain_pos, nnz, E, LPV, (int32_t)n_tiles, TR, d_first_visit, T.d_dir_sets, T.d_rec, T.d_extra,
+                       T.d_ovf);
     MAXK_TRY_CLEAN(hipGetLastError());
     MAXK_TRY_CLEAN(hipStreamSynchronize(s));
 #undef MAXK_TRY_CLEAN
@@ -808,7 +836,8 @@ maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, 
     a.dir_sets = T.d_dir_sets;
     a.rec = T.d_rec;
     a.extra = T.d_extra;
-    a.chain = T.d_chain;
+    a.ovf = T.d_ovf;
+    a.ovf_dir = T.d_ovf_dir;
     a.N = N;
     a.dim = dim;
     a.k = k;
