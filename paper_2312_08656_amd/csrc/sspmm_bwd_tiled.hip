@@ -201,7 +201,7 @@ struct TiledArgs {
     int32_t atomic_out;
 };
 
-// PPL (4 or 8) consecutive sp_index entries, fetched with as few loads as their width allows
+// PPL (= 4) consecutive sp_index entries, fetched with one load
 template <typename IdxT, int PPL>
 struct IdxVec;
 template <>
@@ -211,26 +211,10 @@ struct IdxVec<uint8_t, 4> {
     __device__ __forceinline__ uint32_t get(int i) const { return (w >> (8 * i)) & 0xFFu; }
 };
 template <>
-struct IdxVec<uint8_t, 8> {
-    uint2 w;
-    __device__ __forceinline__ void load(const void* p) { w = *reinterpret_cast<const uint2*>(p); }
-    __device__ __forceinline__ uint32_t get(int i) const { return ((i < 4 ? w.x : w.y) >> (8 * (i & 3))) & 0xFFu; }
-};
-template <>
 struct IdxVec<uint16_t, 4> {
     uint2 w;
     __device__ __forceinline__ void load(const void* p) { w = *reinterpret_cast<const uint2*>(p); }
     __device__ __forceinline__ uint32_t get(int i) const { return ((i < 2 ? w.x : w.y) >> (16 * (i & 1))) & 0xFFFFu; }
-};
-template <>
-struct IdxVec<uint16_t, 8> {
-    uint4 w;
-    __device__ __forceinline__ void load(const void* p) { w = *reinterpret_cast<const uint4*>(p); }
-    __device__ __forceinline__ uint32_t get(int i) const
-    {
-        const uint32_t x = i < 2 ? w.x : i < 4 ? w.y : i < 6 ? w.z : w.w;
-        return (x >> (16 * (i & 1))) & 0xFFFFu;
-    }
 };
 template <>
 struct IdxVec<int32_t, 4> {
@@ -238,28 +222,13 @@ struct IdxVec<int32_t, 4> {
     __device__ __forceinline__ void load(const void* p) { w = *reinterpret_cast<const uint4*>(p); }
     __device__ __forceinline__ uint32_t get(int i) const { return i == 0 ? w.x : i == 1 ? w.y : i == 2 ? w.z : w.w; }
 };
-template <>
-struct IdxVec<int32_t, 8> {
-    uint4 w0, w1;
-    __device__ __forceinline__ void load(const void* p)
-    {
-        w0 = reinterpret_cast<const uint4*>(p)[0];
-        w1 = reinterpret_cast<const uint4*>(p)[1];
-    }
-    __device__ __forceinline__ uint32_t get(int i) const
-    {
-        const uint4& w = i < 4 ? w0 : w1;
-        return (i & 3) == 0 ? w.x : (i & 3) == 1 ? w.y : (i & 3) == 2 ? w.z : w.w;
-    }
-};
 
-// TR: source rows per tile (16, 32 or 48);
+// TR: source rows per tile (16 is what the launcher uses: 32 and 48 were measured slower);
 // DIMC: hidden width when known at compile time (LDS and row offsets become immediates), 0 = a.dim;
-// RC: 256-column chunks that cover a dY row (dim <= RC * 256); PPL: CBSR positions per lane (4 or 8)
+// RC: 256-column chunks that cover a dY row (dim <= RC * 256); PPL: CBSR positions per lane (4; 8 was measured slower)
 //
-// A wavefront on its own issues at most one instruction every four clocks or so, and every SIMD here hosts one
-// accumulating and one loading wavefront, so the instruction count per tile and per set is what this kernel's time
-// follows: addresses are kept as a uniform base (scalar registers, advanced with scalar adds) plus a fixed 32-bit lane
+// A wavefront on its own issues at most one instruction every four clocks or so, and a tile's few sets are each one
+// wavefront's work, so the instruction count per tile and per set is what this kernel's time follows: addresses are kept as a uniform base (scalar registers, advanced with scalar adds) plus a fixed 32-bit lane
 // offset, the lists are padded so that reading ahead needs no clamping, and nothing is recomputed per tile.
 template <int TR, int DIMC, int RC, int PPL, typename IdxT>
 __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArgs a)
