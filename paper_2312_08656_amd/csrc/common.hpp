@@ -62,12 +62,14 @@ constexpr int kSlabLongVisit = 32;
 struct TiledSet {
     int32_t D = 0, TR = 0, E = 0, LPV = 0;  // destinations per set; rows per tile; visits per wave instruction; lanes per visit
     int32_t n_dsets = 0, n_tiles = 0;
+    int32_t G = 0, R = 0, tiles_per_range = 0;  // destination sets per XCD; source ranges; tiles per range
+    int32_t ovf_by_bucket = 0;                  // overflow entries: added bucket by bucket (1) or with LDS atomics (0)
     int64_t total_sets = 0, n_visits = 0, n_chain = 0;
     uint32_t* d_dir_sets = nullptr;  // [n_dsets * n_tiles + 1 (+ spare)] first wave instruction of each list
     uint2* d_rec = nullptr;          // [total_sets * E] visit records (first entry inline)
     uint4* d_extra = nullptr;        // [total_sets * E] second and third entry of a visit
     uint4* d_ovf = nullptr;          // [n_chain + 1] fourth and later entries of a visit (added at the end of the kernel)
-    uint32_t* d_ovf_dir = nullptr;   // [n_dsets * n_tiles + 1] overflow entries before every (destination set, tile)
+    uint32_t* d_ovf_dir = nullptr;   // [n_dsets * R * lane groups + 1] overflow entries before every (workgroup, lane group)
     uint32_t* d_progress = nullptr;  // [8 * ceil(n_dsets / 8) * 32] progress marks of the running workgroups (pacing)
 };
 

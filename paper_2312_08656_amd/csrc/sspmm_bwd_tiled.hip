@@ -36,6 +36,8 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <new>
+#include <vector>
 
 #include <rocprim/rocprim.hpp>
 
@@ -101,14 +103,12 @@ __global__ __launch_bounds__(256) void tiled_flags_kernel(const uint64_t* __rest
     }
 }
 
-// sets[g] = wave instructions that the visits of group g need; first_visit[g] = visits before group g;
-// ovf_dir[g] = overflow entries (fourth and later entries of a visit) before group g
+// sets[g] = wave instructions that the visits of group g need; first_visit[g] = visits before group g
 __global__ __launch_bounds__(256) void tiled_groups_kernel(const uint64_t* __restrict__ key,
-                                                           const uint32_t* __restrict__ rank,
-                                                           const uint32_t* __restrict__ chain_pos, int64_t nnz,
+                                                           const uint32_t* __restrict__ rank, int64_t nnz,
                                                            int64_t n_groups, int32_t E, uint32_t n_visits,
-                                                           uint32_t n_ovf, uint32_t* __restrict__ first_visit,
-                                                           uint32_t* __restrict__ sets, uint32_t* __restrict__ ovf_dir)
+                                                           uint32_t* __restrict__ first_visit,
+                                                           uint32_t* __restrict__ sets)
 {
     const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (g > n_groups) return;
@@ -121,10 +121,8 @@ __global__ __launch_bounds__(256) void tiled_groups_kernel(const uint64_t* __res
         return lo;
     };
     auto visits_before = [&](int64_t pos) { return pos < nnz ? rank[pos] - 1u : n_visits; };
-    const int64_t pos = lower((uint64_t)g << 18);
-    const uint32_t fv = visits_before(pos);
+    const uint32_t fv = visits_before(lower((uint64_t)g << 18));
     first_visit[g] = fv;
-    ovf_dir[g] = pos < nnz ? chain_pos[pos] : n_ovf;
     if (g < n_groups) {
         const uint32_t nv = visits_before(lower((uint64_t)(g + 1) << 18)) - fv;
         sets[g] = (nv + (uint32_t)E - 1u) / (uint32_t)E;
@@ -146,10 +144,11 @@ __global__ __launch_bounds__(256) void tiled_records_kernel(const uint64_t* __re
                                                             const uint32_t* __restrict__ late,
                                                             const uint32_t* __restrict__ chain_pos, int64_t nnz,
                                                             int32_t E, int32_t LPV, int32_t n_tiles, int32_t tile_rows,
+                                                            int32_t n_ranges, int32_t tiles_per_range, int32_t n_owners,
                                                             const uint32_t* __restrict__ first_visit,
                                                             const uint32_t* __restrict__ dir_sets,
                                                             uint2* __restrict__ rec, uint4* __restrict__ extra,
-                                                            uint4* __restrict__ ovf)
+                                                            uint4* __restrict__ ovf, uint64_t* __restrict__ ovf_key)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
@@ -173,12 +172,45 @@ __global__ __launch_bounds__(256) void tiled_records_kernel(const uint64_t* __re
             }
         } else if (late[p]) {
             // fourth and later entries of a visit (rare) are not worked on tile by tile: the kernel adds them at the end,
-            // straight from dY.  {weight, source row, destination within the set}
-            const uint32_t tile = (uint32_t)((kp >> 18) % (uint64_t)n_tiles);
-            ovf[chain_pos[p]] = make_uint4(__float_as_uint(val[p]), tile * (uint32_t)tile_rows + il,
-                                           (uint32_t)((kp >> 6) & 0xFFFu), 0u);
+            // straight from dY.  {weight, source row, destination within the set}; they are then sorted by
+            // (workgroup = destination set and source range, owner = the lane group that adds them, destination)
+            const uint64_t g = kp >> 18;
+            const uint32_t tile = (uint32_t)(g % (uint64_t)n_tiles), dset = (uint32_t)(g / (uint64_t)n_tiles);
+            const uint32_t jl = (uint32_t)((kp >> 6) & 0xFFFu);
+            const uint32_t range = tile / (uint32_t)tiles_per_range, tl = tile - range * (uint32_t)tiles_per_range;
+            const uint64_t bucket = ((uint64_t)dset * (uint64_t)n_ranges + range) * (uint64_t)n_owners + jl % (uint32_t)n_owners;
+            ovf[chain_pos[p]] = make_uint4(__float_as_uint(val[p]), tile * (uint32_t)tile_rows + il, jl, 0u);
+            ovf_key[chain_pos[p]] = (bucket << 32) | ((uint64_t)jl << 20) | (uint64_t)(((tl << 6) | il) & 0xFFFFFu);
         }
     }
+}
+
+__global__ __launch_bounds__(256) void tiled_iota_kernel(uint32_t* __restrict__ p, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = (uint32_t)i;
+}
+
+__global__ __launch_bounds__(256) void tiled_ovf_gather_kernel(const uint32_t* __restrict__ order,
+                                                               const uint4* __restrict__ in, int64_t n,
+                                                               uint4* __restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) out[i] = in[order[i]];
+}
+
+// dir[b] = overflow entries in buckets below b (b = 0 .. n_buckets)
+__global__ __launch_bounds__(256) void tiled_ovf_dir_kernel(const uint64_t* __restrict__ key, int64_t n, int64_t n_buckets,
+                                                            uint32_t* __restrict__ dir)
+{
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b > n_buckets) return;
+    int64_t lo = 0, hi = n;  // first entry whose bucket is >= b
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)(key[mid] >> 32) < b) lo = mid + 1; else hi = mid;
+    }
+    dir[b] = (uint32_t)lo;
 }
 
 // ----------------------------------------------------------------------- kernel ----
@@ -191,7 +223,7 @@ struct TiledArgs {
     const uint2* rec;          // [total_sets * E] visit records
     const uint4* extra;        // [total_sets * E] second and third entry of a visit, where it has them
     const uint4* ovf;          // fourth and later entries of a visit: {weight, source row, destination within its set}
-    const uint32_t* ovf_dir;   // [n_dsets * n_tiles + 1] overflow entries before every (destination set, tile)
+    const uint32_t* ovf_dir;   // [(n_dsets * R) * lane groups + 1] overflow entries before every (workgroup, lane group)
     int64_t N;
     int32_t dim, k;
     int32_t D, n_dsets, n_tiles;
@@ -199,6 +231,7 @@ struct TiledArgs {
     uint32_t* progress;             // [8 * G * R] tiles swept so far by every workgroup (0 = not started, ~0 = done)
     int32_t window;                 // tiles a workgroup may be ahead of the slowest one of its pack; 0 = no pacing
     int32_t atomic_out;
+    int32_t ovf_by_bucket;  // how the overflow entries are added at the end (see there)
 };
 
 // PPL (= 4) consecutive sp_index entries, fetched with one load
@@ -577,33 +610,65 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
     __syncthreads();
     {
         // Overflow entries of this (source range, destination set): fourth and later entries of a visit.  They are few
-        // (1 visit in 7,000 on the dense workload has any), so they are not chained behind their visit, where the
-        // dependent load would sit on a tile's critical path, but added here: sampled straight from dY, with LDS
-        // atomics, since two of them may belong to one destination.  Same lane layout as a set: k/4 lanes per entry.
+        // (1 visit in 8,000 on the dense workload has any), so they are not chained behind their visit, where the
+        // dependent load would sit on a tile's critical path, but added here, sampled straight from dY.  They come
+        // sorted into one bucket per lane group (k/4 lanes, as in a set), a destination always in the same bucket, so
+        // a lane group can add its entries one after the other with plain LDS read-add-writes and nobody else touches
+        // those accumulators (LDS atomics retire about one lane in 3 clocks here); which of the two ways below is
+        // taken is decided when the lists are built, from the number of entries and the longest bucket.
         const int LPV = k / PPL, E = kWave / LPV, g = lane / LPV, q = lane - g * LPV;
-        const uint32_t o0 = a.ovf_dir[(int64_t)d * a.n_tiles + t0], o1 = a.ovf_dir[(int64_t)d * a.n_tiles + t1];
-        if (g < E && o0 < o1) {
-            // three stages in flight, so that an iteration waits for one round trip, not three: the record two
-            // iterations ahead, the destination's columns one ahead, the samples of the current one (reads past the
-            // end are clamped to the last entry and dropped)
-            const uint32_t stride = (uint32_t)((kTiledThreads / kWave) * E), last = o1 - 1;
-            const IdxT* const ib = reinterpret_cast<const IdxT*>(a.sp_index) + (dest0 * (int64_t)k + q * PPL);
-            uint32_t e = o0 + (uint32_t)(wave * E + g);
-            uint4 r0 = a.ovf[min(e, last)], r1 = a.ovf[min(e + stride, last)];
-            IdxVec<IdxT, PPL> i0;
-            i0.load(ib + (int64_t)r0.z * k);
-            for (; e < o1; e += stride) {
-                const uint4 r2 = a.ovf[min(e + 2 * stride, last)];
-                IdxVec<IdxT, PPL> i1;
-                i1.load(ib + (int64_t)r1.z * k);
-                const float w = __uint_as_float(r0.x);
-                const float* __restrict__ row = a.dY + (int64_t)r0.y * dim;
-                float x[PPL];
+        const int n_owners = (kTiledThreads / kWave) * E;
+        const int64_t bucket0 = ((int64_t)d * a.R + range) * n_owners;
+        const IdxT* const ib = reinterpret_cast<const IdxT*>(a.sp_index) + (dest0 * (int64_t)k + q * PPL);
+        if (g < E && a.ovf_by_bucket) {
+            // Mode 1 (many overflow entries, spread evenly: small dense graphs): every lane group adds its own bucket.
+            const uint32_t b0 = a.ovf_dir[bucket0 + (wave * E + g)], b1 = a.ovf_dir[bucket0 + (wave * E + g) + 1];
+            if (b0 < b1) {
+                // two stages ahead of the adds: the next record, and the next destination's columns (reads past the
+                // end are clamped to the last entry and dropped)
+                const uint32_t last = b1 - 1;
+                uint4 r0 = a.ovf[b0], r1 = a.ovf[min(b0 + 1, last)];
+                IdxVec<IdxT, PPL> i0;
+                i0.load(ib + (int64_t)r0.z * k);
+                for (uint32_t e = b0; e < b1; ++e) {
+                    const uint4 r2 = a.ovf[min(e + 2, last)];
+                    IdxVec<IdxT, PPL> i1;
+                    i1.load(ib + (int64_t)r1.z * k);
+                    const float w = __uint_as_float(r0.x);
+                    const float* __restrict__ row = a.dY + (int64_t)r0.y * dim;
+                    float x[PPL];
 #pragma unroll
-                for (int c = 0; c < PPL; ++c) x[c] = row[i0.get(c)];
+                    for (int c = 0; c < PPL; ++c) x[c] = row[i0.get(c)];
+                    float4* const ap = reinterpret_cast<float4*>(acc + (r0.z * k + q * PPL));
+                    float4 av = *ap;
+                    av.x += w * x[0]; av.y += w * x[1]; av.z += w * x[2]; av.w += w * x[3];
+                    *ap = av;
+                    r0 = r1; r1 = r2; i0 = i1;
+                }
+            }
+        } else if (g < E) {
+            // Mode 2 (few overflow entries, but hub destinations with hundreds of them in one bucket: large graphs):
+            // the workgroup's entries are dealt to the lane groups in turn and added with LDS atomics.
+            const uint32_t o0 = a.ovf_dir[bucket0], o1 = a.ovf_dir[bucket0 + n_owners];
+            if (o0 < o1) {
+                const uint32_t stride = (uint32_t)n_owners, last = o1 - 1;
+                uint32_t e = o0 + (uint32_t)(wave * E + g);
+                uint4 r0 = a.ovf[min(e, last)], r1 = a.ovf[min(e + stride, last)];
+                IdxVec<IdxT, PPL> i0;
+                i0.load(ib + (int64_t)r0.z * k);
+                for (; e < o1; e += stride) {
+                    const uint4 r2 = a.ovf[min(e + 2 * stride, last)];
+                    IdxVec<IdxT, PPL> i1;
+                    i1.load(ib + (int64_t)r1.z * k);
+                    const float w = __uint_as_float(r0.x);
+                    const float* __restrict__ row = a.dY + (int64_t)r0.y * dim;
+                    float x[PPL];
 #pragma unroll
-                for (int c = 0; c < PPL; ++c) atomicAdd(&acc[r0.z * k + q * PPL + c], w * x[c]);
-                r0 = r1; r1 = r2; i0 = i1;
+                    for (int c = 0; c < PPL; ++c) x[c] = row[i0.get(c)];
+#pragma unroll
+                    for (int c = 0; c < PPL; ++c) atomicAdd(&acc[r0.z * k + q * PPL + c], w * x[c]);
+                    r0 = r1; r1 = r2; i0 = i1;
+                }
             }
         }
     }
@@ -673,6 +738,23 @@ bool tiled_shape(int64_t N, int dim, int k, TiledShape& sh)
 }
 
 // Builds the visit lists for destination sets of D nodes and k/4 lanes per visit.  Synchronises the device.
+// An XCD holds G destination sets and runs 32 workgroups at a time; the source rows are cut into R ranges so that
+// its G * R workgroups fill whole rounds of 32 (as nearly as a small R allows).
+void tiled_ranges(int n_dsets, int n_tiles, int& G, int& R, int& tiles_per_range)
+{
+    G = (n_dsets + 7) / 8;
+    int best_r = 1;
+    double best_fill = 0.0;
+    for (int r = 1; r <= 32; ++r) {
+        const int units = G * r;
+        const double fill = (double)units / (32.0 * ((units + 31) / 32));
+        if (fill > best_fill + 0.02) { best_fill = fill; best_r = r; }
+    }
+    R = std::min<int>(best_r, std::max<int>(1, n_tiles / 8));
+    tiles_per_range = (n_tiles + R - 1) / R;
+    R = (n_tiles + tiles_per_range - 1) / tiles_per_range;
+}
+
 maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_csc_ptr, const int32_t* d_csc_src,
                         const float* d_csc_val, int D, int TR, int k)
 {
@@ -685,12 +767,15 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
     uint64_t *d_key = nullptr, *d_key_sorted = nullptr;
     float* d_val_sorted = nullptr;
     uint32_t *d_head = nullptr, *d_rank = nullptr, *d_late = nullptr, *d_chain_pos = nullptr, *d_first_visit = nullptr,
-             *d_sets = nullptr;
+             *d_sets = nullptr, *d_ovf_order = nullptr, *d_ovf_order_sorted = nullptr;
+    uint64_t *d_ovf_key = nullptr, *d_ovf_key_sorted = nullptr;
+    uint4* d_ovf_unsorted = nullptr;
     void* d_tmp = nullptr;
     auto cleanup = [&]() {
         (void)hipFree(d_key); (void)hipFree(d_key_sorted); (void)hipFree(d_val_sorted); (void)hipFree(d_head);
         (void)hipFree(d_rank); (void)hipFree(d_late); (void)hipFree(d_chain_pos); (void)hipFree(d_first_visit);
-        (void)hipFree(d_sets); (void)hipFree(d_tmp);
+        (void)hipFree(d_sets); (void)hipFree(d_tmp); (void)hipFree(d_ovf_order); (void)hipFree(d_ovf_order_sorted);
+        (void)hipFree(d_ovf_key); (void)hipFree(d_ovf_key_sorted); (void)hipFree(d_ovf_unsorted);
     };
 #define MAXK_TRY_CLEAN(expr)                                                           \
     do {                                                                               \
@@ -742,10 +827,8 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
     MAXK_TRY_CLEAN(hipMalloc((void**)&d_sets, sizeof(uint32_t) * (size_t)(n_groups + 1)));
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_dir_sets, sizeof(uint32_t) * (size_t)(n_groups + 4)));
     MAXK_TRY_CLEAN(hipMemsetAsync(T.d_dir_sets + n_groups, 0xFF, sizeof(uint32_t) * 4, s));  // spare entries: read, never used
-    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_ovf_dir, sizeof(uint32_t) * (size_t)(n_groups + 1)));
     hipLaunchKernelGGL(tiled_groups_kernel, dim3((unsigned)((n_groups + 1 + 255) / 256)), dim3(256), 0, s, d_key_sorted,
-                       d_rank, d_chain_pos, nnz, n_groups, E, n_visits, (uint32_t)n_chain, d_first_visit, d_sets,
-                       T.d_ovf_dir);
+                       d_rank, nnz, n_groups, E, n_visits, d_first_visit, d_sets);
     MAXK_TRY_CLEAN(hipGetLastError());
     tmp_bytes = 0;
     MAXK_TRY_CLEAN(rocprim::exclusive_scan(nullptr, tmp_bytes, d_sets, T.d_dir_sets, 0u, (size_t)(n_groups + 1),
@@ -765,17 +848,63 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
     const int64_t n_slots = ((int64_t)total_sets + (kRecAhead + 1) * kAccWaves) * E;
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_rec, sizeof(uint2) * (size_t)std::max<int64_t>(n_slots, 1)));
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_extra, sizeof(uint4) * (size_t)std::max<int64_t>(n_slots, 1)));
+    // overflow entries: written in visit order, then sorted into one bucket per (workgroup, lane group of the workgroup)
+    int G = 0, R = 0, tiles_per_range = 0;
+    tiled_ranges((int)n_dsets, (int)n_tiles, G, R, tiles_per_range);
+    const int n_owners = (kTiledThreads / kWave) * E;
+    const int64_t n_buckets = n_dsets * R * (int64_t)n_owners;
+    if (n_buckets + 1 > ((int64_t)1 << 31)) { cleanup(); free_tiled(T); return MAXK_UNSUPPORTED; }
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_ovf, sizeof(uint4) * (size_t)(n_chain + 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_ovf_unsorted, sizeof(uint4) * (size_t)(n_chain + 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&d_ovf_key, sizeof(uint64_t) * (size_t)(n_chain + 1)));
+    MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_ovf_dir, sizeof(uint32_t) * (size_t)(n_buckets + 1)));
     MAXK_TRY_CLEAN(hipMalloc((void**)&T.d_progress, sizeof(uint32_t) * (size_t)(kMaxUnits((int)n_dsets) * kMarkStride)));  // (T.n_dsets is set below)
     hipLaunchKernelGGL(tiled_fill_null_kernel, dim3((unsigned)std::min<int64_t>((n_slots + 255) / 256 + 1, 65536)), dim3(256),
                        0, s, T.d_rec, n_slots);
     hipLaunchKernelGGL(tiled_records_kernel, dim3(blocks), dim3(256), 0, s, d_key_sorted, d_val_sorted, d_head, d_rank,
-                       d_late, d_chain_pos, nnz, E, LPV, (int32_t)n_tiles, TR, d_first_visit, T.d_dir_sets, T.d_rec, T.d_extra,
-                       T.d_ovf);
+                       d_late, d_chain_pos, nnz, E, LPV, (int32_t)n_tiles, TR, R, tiles_per_range, n_owners, d_first_visit,
+                       T.d_dir_sets, T.d_rec, T.d_extra, d_ovf_unsorted, d_ovf_key);
+    MAXK_TRY_CLEAN(hipGetLastError());
+    if (n_chain > 0) {
+        MAXK_TRY_CLEAN(hipMalloc((void**)&d_ovf_key_sorted, sizeof(uint64_t) * (size_t)n_chain));
+        MAXK_TRY_CLEAN(hipMalloc((void**)&d_ovf_order, sizeof(uint32_t) * (size_t)n_chain));
+        MAXK_TRY_CLEAN(hipMalloc((void**)&d_ovf_order_sorted, sizeof(uint32_t) * (size_t)n_chain));
+        hipLaunchKernelGGL(tiled_iota_kernel, dim3((unsigned)std::min<int64_t>((n_chain + 255) / 256, 65536)), dim3(256), 0, s,
+                           d_ovf_order, n_chain);
+        MAXK_TRY_CLEAN(hipGetLastError());
+        (void)hipFree(d_tmp); d_tmp = nullptr;
+        tmp_bytes = 0;
+        MAXK_TRY_CLEAN(rocprim::radix_sort_pairs(nullptr, tmp_bytes, d_ovf_key, d_ovf_key_sorted, d_ovf_order,
+                                                 d_ovf_order_sorted, (size_t)n_chain, 0, 64, s));
+        MAXK_TRY_CLEAN(hipMalloc(&d_tmp, tmp_bytes ? tmp_bytes : 16));
+        MAXK_TRY_CLEAN(rocprim::radix_sort_pairs(d_tmp, tmp_bytes, d_ovf_key, d_ovf_key_sorted, d_ovf_order,
+                                                 d_ovf_order_sorted, (size_t)n_chain, 0, 64, s));
+        hipLaunchKernelGGL(tiled_ovf_gather_kernel, dim3((unsigned)std::min<int64_t>((n_chain + 255) / 256, 65536)), dim3(256),
+                           0, s, d_ovf_order_sorted, d_ovf_unsorted, n_chain, T.d_ovf);
+        MAXK_TRY_CLEAN(hipGetLastError());
+    }
+    hipLaunchKernelGGL(tiled_ovf_dir_kernel, dim3((unsigned)((n_buckets + 1 + 255) / 256)), dim3(256), 0, s,
+                       n_chain > 0 ? d_ovf_key_sorted : d_ovf_key, n_chain, n_buckets, T.d_ovf_dir);
     MAXK_TRY_CLEAN(hipGetLastError());
     MAXK_TRY_CLEAN(hipStreamSynchronize(s));
+    int ovf_by_bucket = 0;
+    if (n_chain > 0 && n_buckets <= ((int64_t)1 << 24)) {
+        // bucket by bucket costs about one memory round trip (~1500 clocks) per entry of the longest bucket, the
+        // atomics about 3 clocks per element of a workgroup's share
+        try {
+            std::vector<uint32_t> h_dir((size_t)n_buckets + 1);
+            MAXK_TRY_CLEAN(hipMemcpy(h_dir.data(), T.d_ovf_dir, sizeof(uint32_t) * h_dir.size(), hipMemcpyDeviceToHost));
+            uint32_t longest = 0;
+            for (int64_t b2 = 0; b2 < n_buckets; ++b2) longest = std::max(longest, h_dir[(size_t)b2 + 1] - h_dir[(size_t)b2]);
+            const double by_bucket = 1500.0 * longest, by_atomics = 3.0 * k * (double)n_chain / (double)(n_dsets * R);
+            ovf_by_bucket = by_bucket < by_atomics ? 1 : 0;
+        } catch (const std::bad_alloc&) {
+            ovf_by_bucket = 0;  // the atomics need no look at the buckets
+        }
+    }
 #undef MAXK_TRY_CLEAN
     cleanup();
+    T.ovf_by_bucket = ovf_by_bucket;
     T.D = D;
     T.TR = TR;
     T.E = E;
@@ -785,6 +914,9 @@ maxk_status build_tiled(TiledSet& T, int64_t N, int64_t nnz, const int32_t* d_cs
     T.total_sets = total_sets;
     T.n_visits = n_visits;
     T.n_chain = n_chain;
+    T.G = G;
+    T.R = R;
+    T.tiles_per_range = tiles_per_range;
     return MAXK_OK;
 }
 
@@ -807,25 +939,16 @@ maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, 
     a.extra = T.d_extra;
     a.ovf = T.d_ovf;
     a.ovf_dir = T.d_ovf_dir;
+    a.ovf_by_bucket = T.ovf_by_bucket;
     a.N = N;
     a.dim = dim;
     a.k = k;
     a.D = T.D;
     a.n_dsets = T.n_dsets;
     a.n_tiles = T.n_tiles;
-    // An XCD holds G destination sets and runs 32 workgroups at a time; the source rows are cut into R ranges so that
-    // its G * R units fill whole rounds of 32 (as nearly as a small R allows).
-    a.G = (T.n_dsets + 7) / 8;
-    int best_r = 1;
-    double best_fill = 0.0;
-    for (int r = 1; r <= 32; ++r) {
-        const int units = a.G * r;
-        const double fill = (double)units / (32.0 * ((units + 31) / 32));
-        if (fill > best_fill + 0.02) { best_fill = fill; best_r = r; }
-    }
-    a.R = std::min<int>(best_r, std::max<int>(1, T.n_tiles / 8));
-    a.tiles_per_range = (T.n_tiles + a.R - 1) / a.R;
-    a.R = (T.n_tiles + a.tiles_per_range - 1) / a.tiles_per_range;
+    a.G = T.G;  // fixed when the lists were built: the overflow entries are sorted by workgroup
+    a.R = T.R;
+    a.tiles_per_range = T.tiles_per_range;
     a.atomic_out = a.R > 1;
     if (a.atomic_out) {
         const maxk_status st = launch_fill_zero(dXs, N * (int64_t)k, s);
