@@ -232,6 +232,7 @@ struct TiledArgs {
     int32_t window;                 // tiles a workgroup may be ahead of the slowest one of its pack; 0 = no pacing
     int32_t atomic_out;
     int32_t ovf_by_bucket;  // how the overflow entries are added at the end (see there)
+    int32_t range_per_xcd;  // workgroup-to-(range, destination set) mapping (see the kernel's first lines)
 };
 
 // PPL (= 4) consecutive sp_index entries, fetched with one load
@@ -276,8 +277,24 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
     // destination set) units range by range, so the 32 workgroups that are resident on it together sweep the same
     // one or two source ranges at the same pace, and a dY row is pulled into that XCD's L2 once per range.
     const int b = blockIdx.x, xcd = b & 7, m = b >> 3;
-    const int range = m / a.G, gi = m - range * a.G;
-    const int d = xcd + 8 * gi;
+    // Two ways from (XCD, position m on it) to (source range, destination set).  When all workgroups are resident at
+    // once and R divides 8 (`range_per_xcd`), an XCD sweeps ONE range - XCD x takes range x % R and every (8/R)-th
+    // destination set - so its 32 workgroups share one stream of rows through its L2 instead of R streams.
+    // Otherwise the XCD takes its G destination sets range after range.  `pack_slot` of `pack_size`: this
+    // workgroup among those that sweep its range on its XCD.
+    int range, d, pack_slot, pack_size, pack_id;
+    if (a.range_per_xcd) {
+        const int per = 8 / a.R;
+        range = xcd % a.R;
+        d = xcd / a.R + per * m;
+        pack_slot = m; pack_size = a.G * a.R; pack_id = xcd;
+    } else {
+        range = m / a.G;
+        pack_slot = m - range * a.G;
+        d = xcd + 8 * pack_slot;
+        pack_size = a.G; pack_id = range * 8 + xcd;
+    }
+    const int gi = pack_slot;
     if (range >= a.R || d >= a.n_dsets) return;
     const int t0 = range * a.tiles_per_range, t1 = min(a.n_tiles, t0 + a.tiles_per_range);
     if (t0 >= t1) return;
@@ -302,7 +319,7 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         // G times as many misses in flight.  The loaded values are not used.
         constexpr int PG = kPrefetchGroupRows / TR > 0 ? kPrefetchGroupRows / TR : 1;  // tiles per prefetch round
         constexpr int PA = kPrefetchAheadRows / TR;                                     // tiles ahead
-        const int pack = min(a.G, 32);  // workgroups that share the lines of a round
+        const int pack = min(pack_size, 32);  // workgroups that share the lines of a round
         const int64_t row_bytes = (int64_t)dim * 4, total_bytes = a.N * row_bytes;
         const int64_t lines_per_group = (PG * TR * row_bytes + 127) / 128;
         const int pf_loads = pack >= 8 ? (int)min((int64_t)4, (lines_per_group / pack + kWave - 1) / kWave) : 0;
@@ -314,9 +331,10 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         // tiles ahead of the slowest nap here, ahead of the barrier, which holds their whole workgroup.  The naps are
         // bounded whatever the others do, so every wavefront reaches the end.
         // (a mark has a cache line to itself: with several in one line, the writers of the others hold up every reader)
-        uint32_t* const my_mark = a.progress + ((int64_t)(range * 8 + xcd) * a.G + gi) * kMarkStride;
-        const uint32_t* const pack_marks = a.progress + (int64_t)(range * 8 + xcd) * a.G * kMarkStride;
-        const bool member = lane < a.G && xcd + 8 * lane < a.n_dsets;  // lane l looks at destination set xcd + 8 l
+        uint32_t* const my_mark = a.progress + ((int64_t)pack_id * pack_size + pack_slot) * kMarkStride;
+        const uint32_t* const pack_marks = a.progress + (int64_t)pack_id * pack_size * kMarkStride;
+        // lane l looks at the workgroup in slot l of the pack (if that slot has a destination set at all)
+        const bool member = lane < pack_size && (a.range_per_xcd ? xcd / a.R + (8 / a.R) * lane : xcd + 8 * lane) < a.n_dsets;
         const uint32_t* const my_view = pack_marks + (member ? lane : gi) * kMarkStride;  // every lane loads, so that no branch (and
         uint32_t seen_next = 0xFFFFFFFFu;                                   // no conservative wait) surrounds the load
         int countdown = 0;
@@ -950,6 +968,7 @@ maxk_status launch_bwd_tiled(const TiledSet& T, const void* dY, int value_type, 
     a.R = T.R;
     a.tiles_per_range = T.tiles_per_range;
     a.atomic_out = a.R > 1;
+    a.range_per_xcd = (a.R > 1 && 8 % a.R == 0 && a.G * a.R <= 32) ? 1 : 0;
     if (a.atomic_out) {
         const maxk_status st = launch_fill_zero(dXs, N * (int64_t)k, s);
         if (st != MAXK_OK) return st;
