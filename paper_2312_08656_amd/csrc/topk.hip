@@ -4,14 +4,16 @@
 // (E values per lane).  The paper's kernel bisects a floating-point pivot
 // between min and max and stops after at most 10 rounds, which cannot separate
 // equal values at rank k.  Here the selection is EXACT, in two stages.
-// Stage 1 is the paper's idea made exact: bisect a pivot on the value axis
-// between -max|x| and +max|x|, but stop only when the pivot keeps exactly k
-// entries (any such pivot gives the one correct set); a step is E compares + E
-// wave ballots + scalar popcounts, no LDS and no barrier, and for continuous
-// data about 8 steps are enough whatever the exponent range (the step count
-// is log2(range / gap at rank k)).  The kernel is bound by scalar-unit issue
-// (~12 scalar instructions per step, one scalar instruction per clock per CU),
-// so halving the steps is what halves its time.
+// Stage 1 is the paper's idea made exact: move a pivot on the value axis, but
+// stop only when the pivot keeps exactly k entries (any such pivot gives the
+// one correct set); a step is E compares + E wave ballots + scalar popcounts,
+// no LDS and no barrier.  A search that bisects [-max|x|, +max|x|] needs about
+// 8 steps on continuous data whatever the exponent range (log2(range / gap at
+// rank k)); one that starts at the pivot of the row before needs about 5.5 when
+// neighbouring rows are alike, and up to 7 more than the bisection when they
+// are not (the step doubles until the count changes sides).  The kernel is bound by scalar-unit issue (~12 scalar instructions per
+// step, one scalar instruction per clock per CU), so fewer steps is what
+// shortens it.
 // Stage 2 runs only for rows stage 1 cannot settle (ties at rank k, infinities,
 // k = dim): a most-significant-bit-first radix descent on order-preserving
 // integer keys finds the k-th largest value itself, and ties at that value are
@@ -92,7 +94,17 @@ __device__ __forceinline__ void column_order_prefix(const bool (&flag)[E], int (
     }
 }
 
-constexpr int kPivotSteps = 16;  // bisection steps before a row is handed to the radix descent (99 % need <= 14)
+constexpr int kPivotSteps = 16;  // pivots tried before a row is handed to the radix descent (99 % need <= 14)
+
+// What a wavefront carries from one row to its next: the pivot that selected the last row is the first one tried on
+// the next.  Rows of one feature matrix mostly have their k-th largest value in about the same place, and a search
+// that starts next to it needs about 5 pivots where one that starts from the row's range needs about 8.  All three
+// fields are wave-uniform.
+struct PivotHint {
+    float pivot = 0.f;                // first pivot to try (clamped to the row's range)
+    float step = 0.5f;                // first step, as a fraction of max|x|
+    uint32_t bracketed = 0x80000000u;  // sign bit set: the target is known to lie within `step` (plain bisection)
+};
 
 // One row of H into registers: chunks of 64*V columns, V consecutive columns per lane.  Lanes past the row hold
 // copies of its last chunk; select_row replaces them.  Nothing here touches the loaded values, so the loads of the
@@ -140,16 +152,14 @@ __device__ __forceinline__ void write_row(const bool (&sel)[E], const float (&v)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    if (k <= kWave) {  // one store of each kind: the usual case, and a fixed number of memory operations
-        if (lane < k) {
-            od[lane] = narrow_value<VT>(__uint_as_float(stage[lane]));
-            oi[lane] = (IdxT)stage[k + lane];
-        }
-    } else {
-        for (int t = lane; t < k; t += kWave) {
-            od[t] = narrow_value<VT>(__uint_as_float(stage[t]));
-            oi[t] = (IdxT)stage[k + t];
-        }
+    // The first 64 survivors: one store of each kind, issued by every lane (lanes past k repeat entry k-1), so that
+    // the number of memory operations in flight never depends on a branch and the waits for the row loads are exact.
+    const int t0 = lane < k ? lane : k - 1;
+    od[t0] = narrow_value<VT>(__uint_as_float(stage[t0]));
+    oi[t0] = (IdxT)stage[k + t0];
+    for (int t = lane + kWave; t < k; t += kWave) {
+        od[t] = narrow_value<VT>(__uint_as_float(stage[t]));
+        oi[t] = (IdxT)stage[k + t];
     }
     __builtin_amdgcn_wave_barrier();  // the next row's survivors go to the same area
 }
@@ -158,7 +168,7 @@ __device__ __forceinline__ void write_row(const bool (&sel)[E], const float (&v)
 // VT: storage format of the values written (MAXK_VALUE_*); selection always works on the fp32 input
 // PAD: the row is shorter than the E*64 columns the lanes cover
 template <int E, int V, bool PAD, int VT, typename IdxT>
-__device__ __forceinline__ void select_row(const float (&raw)[E], int dim, int k, int lane,
+__device__ __forceinline__ void select_row(const float (&raw)[E], int dim, int k, int lane, PivotHint& hint,
                                            uint32_t* __restrict__ stage, value_store_t<VT>* __restrict__ od,
                                            IdxT* __restrict__ oi)
 {
@@ -172,26 +182,47 @@ __device__ __forceinline__ void select_row(const float (&raw)[E], int dim, int k
         amax = fmaxf(amax, in ? fabsf(raw[e]) : 0.f);
     }
 
-    // Stage 1: bisection of a pivot on the value axis, pivot = 0 first, then +- max|x| / 2, / 4, ... until a pivot keeps
-    // exactly k.  The counts are scalar (ballot + scalar popcount).  The pivot and the step are the same in every
-    // lane but are kept in vector registers (the empty asm hides that they are uniform): the compares read them
-    // there, and a scalar copy would cost a move and wait states between dependent vector and scalar instructions
-    // on every step.  The scalar unit's issue rate is what bounds this kernel.
+    // Stage 1: search for a pivot on the value axis that keeps exactly k.  A wavefront's first row starts at pivot 0
+    // and bisects [-max|x|, max|x|] (steps max|x| / 2, / 4, ...).  Later rows start at the pivot of the row before
+    // (clamped to this row's range) with a step of max|x| / 32, which doubles while the count stays on the same
+    // side of k and halves from the first change of side on.  The counts are scalar (ballot + scalar popcount).  The
+    // pivot and the step are the same in every lane but are kept in vector registers (the empty asm hides that they
+    // are uniform): the compares read them there, and a scalar copy would cost a move and wait states between
+    // dependent vector and scalar instructions on every step.  The scalar unit's issue rate is what bounds this
+    // kernel.
     const uint32_t amax_bits = wave_max_nonneg(amax);
     float pivot = 0.f;
     int kept = -1;  // entries the last pivot keeps
-    if (amax_bits < 0x7F800000u && k < dim) {  // finite row (k = dim: every pivot above -max|x| keeps too few)
-        float half = 0.5f * __uint_as_float(amax_bits);
-        asm volatile("" : "+v"(pivot), "+v"(half));
-        for (int step = 0; step < kPivotSteps; ++step) {
+    if (amax_bits - 1u < 0x7F7FFFFFu && k < dim) {  // finite, not all zero (k = dim: every pivot above -max|x| keeps too few)
+        constexpr uint32_t kSign = 0x80000000u;
+        const float row_max = __uint_as_float(amax_bits);
+        pivot = __builtin_amdgcn_fmed3f(hint.pivot, -row_max, row_max);
+        uint32_t step_bits = __float_as_uint(hint.step * row_max);  // the step, signed: + moves the pivot up
+        uint32_t bracketed = hint.bracketed;
+        asm volatile("" : "+v"(pivot), "+v"(step_bits), "+v"(bracketed));
+        const auto count = [&](float p) {
             int cnt = 0;
 #pragma unroll
-            for (int e = 0; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[e] >= pivot));
-            kept = cnt;
-            if (kept == k) break;
-            const uint32_t down = kept > k ? 0u : 0x80000000u;  // too few kept: move the pivot down
-            pivot += __uint_as_float(__float_as_uint(half) ^ down);
-            half *= 0.5f;
+            for (int e = 0; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[e] >= p));
+            return cnt;
+        };
+        kept = count(pivot);
+        if (kept != k) {
+            step_bits |= kept > k ? 0u : kSign;  // too few kept: move the pivot down
+            for (int step = 1; step < kPivotSteps; ++step) {
+                pivot += __uint_as_float(step_bits);
+                kept = count(pivot);
+                if (kept == k) break;
+                const uint32_t down = kept > k ? 0u : kSign;
+                bracketed |= down ^ step_bits;  // (sign bit) the count changed sides: the target is within the last step
+                const float scale = (int32_t)bracketed < 0 ? 0.5f : 2.f;
+                step_bits = __float_as_uint(__uint_as_float((step_bits & ~kSign) | down) * scale);
+            }
+        }
+        if (kept == k) {
+            hint.pivot = pivot;
+            hint.step = 0.03125f;
+            hint.bracketed = 0u;
         }
     }
 
@@ -269,21 +300,27 @@ __global__ __launch_bounds__(256) void topk_cbsr_kernel(const float* __restrict_
     // issues exactly one row load - past the wavefront's last row it re-reads that row - so that the number of
     // memory operations in flight is the same on every path and the waits can be exact.
     float a[E], b[E], c[E];
+    PivotHint hint;
     // rows_per_wave * dim and rows_per_wave * k fit 32 bits (at most 8 rows of at most MAXK_MAX_DIM columns)
 #define MAXK_TOPK_LOAD(buf, i) load_row<E, V>(h0 + ((i) < n ? (i) : n - 1) * dim, dim, lane, buf)
 #define MAXK_TOPK_SELECT(buf, i) \
-    select_row<E, V, PAD, VT, IdxT>(buf, dim, k, lane, stage, od0 + (i) * k, oi0 + (i) * k)
+    select_row<E, V, PAD, VT, IdxT>(buf, dim, k, lane, hint, stage, od0 + (i) * k, oi0 + (i) * k)
     MAXK_TOPK_LOAD(a, 0);
     MAXK_TOPK_LOAD(b, 1);
-    for (int i = 0; i < n; i += 3) {
+    // Whole turns of three rows; the loop is left only at its end (an exit from the middle would reach the loop's
+    // latch with a load still in flight on that path, and the waits of every turn would have to allow for it).
+    int i = 0;
+    for (; i + 2 < n; i += 3) {
         MAXK_TOPK_LOAD(c, i + 2);
         MAXK_TOPK_SELECT(a, i);
-        if (i + 1 >= n) break;
         MAXK_TOPK_LOAD(a, i + 3);
         MAXK_TOPK_SELECT(b, i + 1);
-        if (i + 2 >= n) break;
         MAXK_TOPK_LOAD(b, i + 4);
         MAXK_TOPK_SELECT(c, i + 2);
+    }
+    if (i < n) {  // one or two rows left: they are in a and b
+        MAXK_TOPK_SELECT(a, i);
+        if (i + 1 < n) MAXK_TOPK_SELECT(b, i + 1);
     }
 #undef MAXK_TOPK_LOAD
 #undef MAXK_TOPK_SELECT

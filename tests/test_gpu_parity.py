@@ -155,6 +155,25 @@ def test_topk_row_pipeline_edges_and_value_ranges(N):
         check_topk(H, k, sp_data, sp_index)
 
 
+@pytest.mark.parametrize("dim,k,ib", [(256, 32, 1), (1024, 96, 2), (100, 7, 1)])
+def test_topk_neighbouring_rows_far_apart(dim, k, ib):
+    """A wavefront starts the pivot search of a row at the pivot of the row before it: here every row has another
+    scale and offset than its neighbours (factors of 1e-20..1e20, offsets of either sign, all-zero and constant rows
+    in between), so every such start is far from where the row's own pivot lies, in either direction."""
+    N = 8192 * 8 + 77
+    rng = np.random.default_rng(dim + k)
+    H = synth.normal_matrix(N, dim, seed=dim * 7 + k)
+    scale = np.float32(10.0) ** rng.integers(-20, 21, size=N).astype(np.float32)
+    offset = rng.choice(np.array([0, 0, 1, -1, 50, -50, 1e4, -1e4], np.float32), size=N)
+    H *= scale[:, None]
+    H += (offset * scale)[:, None]
+    H[rng.choice(N, 500, replace=False)] = np.float32(0.0)
+    H[rng.choice(N, 500, replace=False)] = np.float32(-7.5)
+    assert np.isfinite(H).all()
+    sp_data, sp_index = gpu_topk(to_dev(H), k, ib)
+    check_topk(H, k, sp_data, sp_index)
+
+
 def test_empty_graph_empty_rows_duplicates_unsorted_columns():
     # N == 0
     z32 = torch.zeros(1, dtype=torch.int32, device="cuda")
