@@ -485,8 +485,9 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
         const int n_it = first >= u1 ? 0 : (int)((u1 - first + kAccWaves - 1) / kAccWaves);
         int tile = t0;
         uint32_t s_end = dt[t0 + 1];                 // first set past `tile`
-        uint32_t s_end_next = dt[t0 + 2];            // (the directory has two spare entries at its end)
-        const_u32_ptr dt_next = dt + (t0 + 3);       // where the s_end_next after that is read from
+        uint32_t s_end_next = dt[t0 + 2];            // (the directory has three spare entries at its end)
+        uint32_t s_end_after = dt[t0 + 3];           // read one tile before it is looked at: the scalar load has a
+        const_u32_ptr dt_next = dt + (t0 + 4);       // whole tile to arrive, cache miss or not
         // uniform bases + fixed lane offsets (bytes)
         const int64_t set_bytes = (int64_t)E * 8;                               // one set of records
         const int64_t step_bytes = set_bytes * kAccWaves;                       // from one of this wavefront's sets to the next
@@ -539,8 +540,9 @@ __global__ __launch_bounds__(kTiledThreads) void bwd_tiled_kernel(const TiledArg
     {                                                                            \
         ++tile;                                                                  \
         s_end = s_end_next;                                                      \
+        s_end_next = s_end_after;                                                \
         __syncthreads();                                                         \
-        s_end_next = *dt_next++; /* asked for after the barrier */               \
+        s_end_after = *dt_next++; /* asked for after the barrier */              \
     }
 #define MAXK_TILED_SET(RQ, RQ_AHEAD, IQ, XQ, IT)                                                                      \
     {                                                                                                                 \
